@@ -1,0 +1,227 @@
+/*
+ * flexattn.h -- C ABI of libflexattn: the FlexAttention hot path on AMD MI355X (gfx950).
+ *
+ * Paper: "Flex Attention: a Programming Model for Generating Optimized Attention Kernels"
+ * (arXiv 2412.05496).  The library computes
+ *
+ *     FlexAttention(Q, K, V) = softmax( mod( Q K^T * scale ) ) V            (Eq. 1)
+ *
+ * where mod applies a score_mod to every scaled score and then sets the scores whose
+ * mask_mod is false to -inf (section 3.1), with work skipped per block through a BlockMask
+ * (section 4.2) and a paged KV cache addressed through a page table (section 5.1).
+ *
+ * General conventions
+ *   - Every entry point returns an int status (FLEXATTN_OK or a negative FLEXATTN_ERR_*),
+ *     never throws and never aborts.  flexattn_strerror() names a status;
+ *     flexattn_last_hip_error() returns the hipError_t behind the last FLEXATTN_ERR_HIP on
+ *     the calling thread.
+ *   - All tensor, BlockMask and workspace pointers are DEVICE pointers owned by the caller.
+ *     The library allocates and frees nothing.  Pointers inside flexattn_mod_params are
+ *     device pointers as well.  Descriptor structs themselves are host memory, read during
+ *     the call only.
+ *   - Every launch is asynchronous on the caller's stream (`stream` is a hipStream_t passed
+ *     as void*; NULL is the default stream).  No call synchronises.
+ *   - Float tensors are bf16 (Q, K, V, O, dO, dQ, dK, dV) unless stated; LSE is fp32.
+ *     Head dimension D is 64 or 128 and has unit stride; other strides are in ELEMENTS.
+ *   - Grouped-query attention: query head hq reads KV head hq / (Hq / Hkv); mods see hq.
+ *   - A query row whose keys are all masked yields O = 0, LSE = -inf and zero gradients.
+ *   - Results are deterministic run to run (no floating-point atomics).
+ */
+#ifndef FLEXATTN_H
+#define FLEXATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ---------------------------------------------------------------- */
+#define FLEXATTN_OK               0
+#define FLEXATTN_ERR_INVALID_ARG  (-1)   /* null pointer, non-positive size, bad stride, ...      */
+#define FLEXATTN_ERR_UNSUPPORTED  (-2)   /* D, block size or (mask, score) pair not compiled in   */
+#define FLEXATTN_ERR_WORKSPACE    (-3)   /* workspace smaller than *_workspace_bytes() asks for   */
+#define FLEXATTN_ERR_HIP          (-4)   /* a HIP call failed; see flexattn_last_hip_error()      */
+
+/* ---- mask_mod (sections 3.1, 3.2) --------------------------------------------------
+ * A mask_mod is a boolean function of (b, h, q_idx, kv_idx).  The library offers the
+ * paper's primitives and their and_mask / or_mask compositions as a two-term disjunction
+ * of conjunctions:   mask = AND(term0 primitives)  OR  AND(term1 primitives)
+ * encoded as  term0 | (term1 << 8).  term0 == 0 means "no mask" (always true); term1 == 0
+ * means "no second term".
+ */
+#define FLEXATTN_M_CAUSAL          1u   /* q_idx >= kv_idx                                        */
+#define FLEXATTN_M_SLIDING_WINDOW  2u   /* q_idx - kv_idx <= window   (one-sided, as the paper)   */
+#define FLEXATTN_M_DOCUMENT        4u   /* doc_ids[b, q_idx] == doc_ids[b, kv_idx]                */
+#define FLEXATTN_M_PREFIX          8u   /* kv_idx < prefix_len                                    */
+#define FLEXATTN_M_CTX_LEN        16u   /* kv_idx < ctx_lens[b]                                   */
+#define FLEXATTN_MASK_OR(term0, term1) ((uint32_t)(term0) | ((uint32_t)(term1) << 8))
+
+#define FLEXATTN_MASK_NONE                  0u
+#define FLEXATTN_MASK_CAUSAL                FLEXATTN_M_CAUSAL
+#define FLEXATTN_MASK_SLIDING_WINDOW        FLEXATTN_M_SLIDING_WINDOW
+#define FLEXATTN_MASK_SWA_CAUSAL            (FLEXATTN_M_CAUSAL | FLEXATTN_M_SLIDING_WINDOW)
+#define FLEXATTN_MASK_DOCUMENT              FLEXATTN_M_DOCUMENT
+#define FLEXATTN_MASK_DOCUMENT_CAUSAL       (FLEXATTN_M_DOCUMENT | FLEXATTN_M_CAUSAL)
+#define FLEXATTN_MASK_PREFIX_LM             FLEXATTN_MASK_OR(FLEXATTN_M_CAUSAL, FLEXATTN_M_PREFIX)
+#define FLEXATTN_MASK_SWA_CAUSAL_OR_PREFIX  FLEXATTN_MASK_OR(FLEXATTN_MASK_SWA_CAUSAL, FLEXATTN_M_PREFIX)
+#define FLEXATTN_MASK_CTX_LEN               FLEXATTN_M_CTX_LEN
+
+/* ---- score_mod (section 3.1; nested score_mods, section 1.1) -------------------------
+ * A bit set; the selected modifications are applied to the scaled score in this order:
+ *   ALIBI     score + alibi_bias[h] * (q_idx - kv_idx)
+ *   REL_BIAS  score + rel_bias[h, clamp(q_idx - kv_idx, 0, rel_len - 1)]
+ *   SOFTCAP   softcap * tanh(score / softcap)
+ */
+#define FLEXATTN_SCORE_IDENTITY  0u
+#define FLEXATTN_SCORE_ALIBI     1u
+#define FLEXATTN_SCORE_REL_BIAS  2u
+#define FLEXATTN_SCORE_SOFTCAP   4u
+
+/* Values the mods capture.  Only the fields a selected mod uses are read. */
+typedef struct flexattn_mod_params {
+    int32_t        window;        /* SLIDING_WINDOW                                            */
+    int32_t        prefix_len;    /* PREFIX                                                    */
+    float          softcap;       /* SOFTCAP, > 0                                              */
+    int32_t        rel_len;       /* REL_BIAS: row length of rel_bias (<= 1024)                */
+    const int32_t* doc_ids;       /* DOCUMENT: [B, seq] token -> document index                */
+    int64_t        doc_stride_b;  /*           elements between batches (0 = shared row)       */
+    const float*   alibi_bias;    /* ALIBI: [Hq] fp32                                          */
+    const float*   rel_bias;      /* REL_BIAS: [Hq, rel_len] fp32, row-major                   */
+    const int32_t* ctx_lens;      /* CTX_LEN: [B] int32                                        */
+} flexattn_mod_params;
+
+/* A 4-D tensor [batch, head, seq, D] with unit stride in D. */
+typedef struct flexattn_tensor {
+    void*   ptr;
+    int64_t stride_b, stride_h, stride_s;   /* in elements */
+} flexattn_tensor;
+
+/* ---- BlockMask (section 4.2) -------------------------------------------------------
+ * The score matrix is cut into Bq x Bk blocks: NR = q_len / Bq rows and NC = kv_len / Bk
+ * columns of blocks.  A block with every scalar masked is skipped; one with none masked is
+ * FULL (mask_mod is not evaluated in it); any other is PARTIAL.
+ *
+ *   kv_num_blocks      [Bm, Hm, NR]      number of PARTIAL blocks in each row of blocks
+ *   kv_indices         [Bm, Hm, NR, NC]  their column indices, ascending; entries past the
+ *                                        count are 0
+ *   full_kv_num_blocks / full_kv_indices the same for FULL blocks
+ *   q_num_blocks       [Bm, Hm, NC]      PARTIAL blocks of each column of blocks
+ *   q_indices          [Bm, Hm, NC, NR]  their row indices (the transpose the backward walks)
+ *   full_q_num_blocks / full_q_indices   the same for FULL blocks
+ *
+ * Bm is 1 (the mask ignores b) or the batch size; Hm is 1 or the number of QUERY heads.
+ * All arrays are int32, dense, row-major.
+ */
+typedef struct flexattn_blockmask {
+    int32_t  Bm, Hm, q_len, kv_len, Bq, Bk;
+    int32_t* kv_num_blocks;
+    int32_t* kv_indices;
+    int32_t* full_kv_num_blocks;
+    int32_t* full_kv_indices;
+    int32_t* q_num_blocks;
+    int32_t* q_indices;
+    int32_t* full_q_num_blocks;
+    int32_t* full_q_indices;
+} flexattn_blockmask;
+
+/* Problem shape of flex_attention (section 2.1). */
+typedef struct flexattn_dims {
+    int32_t B, Hq, Hkv, q_len, kv_len, D;
+} flexattn_dims;
+
+const char* flexattn_strerror(int status);
+int         flexattn_last_hip_error(void);
+int         flexattn_version(void);
+
+/* 1 if forward/backward kernels for this (mask, score, D) were compiled into the library. */
+int flexattn_is_supported(uint32_t mask_id, uint32_t score_id, int32_t D);
+
+/* ---- BlockMask construction (section 4.2; create_block_mask, section 1.1) ----------
+ * Evaluates mask_mod on every (q_idx, kv_idx) of every block -- brute force, so the result
+ * is exact for any mask -- and fills the eight arrays of `bm` (both orientations).
+ * Requires q_len % Bq == 0 and kv_len % Bk == 0 (otherwise FLEXATTN_ERR_UNSUPPORTED) and
+ * Bq * Bk a multiple of 64.
+ *   stats  nullable device int64[4]: {#partial blocks, #full blocks, #blocks, #unmasked
+ *          scalars}, summed over Bm * Hm.
+ *   ws     device workspace of at least flexattn_blockmask_workspace_bytes() bytes.
+ */
+size_t flexattn_blockmask_workspace_bytes(int32_t Bm, int32_t Hm, int32_t q_len, int32_t kv_len,
+                                          int32_t Bq, int32_t Bk);
+int flexattn_blockmask_build(uint32_t mask_id, const flexattn_mod_params* params,
+                             const flexattn_blockmask* bm, int64_t* stats,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* ---- forward (Eq. 1; forward template of section 4.1; block skipping, full-block
+ * optimisation and indirect block access of section 4.2) -----------------------------
+ * O [B, Hq, q_len, D] bf16 and LSE [B, Hq, q_len] fp32 (natural log of the sum of exp of the
+ * modified, masked, scaled scores; dense, row-major).  `bm` must have been built for the
+ * same mask_id/params, with Bq in {64, 128} and Bk in {64, 128}.  Full blocks are processed
+ * without evaluating mask_mod, partial blocks with it, all other blocks not at all.
+ */
+int flexattn_forward(const flexattn_dims* dims,
+                     const flexattn_tensor* Q, const flexattn_tensor* K, const flexattn_tensor* V,
+                     uint32_t score_id, uint32_t mask_id, const flexattn_mod_params* params,
+                     const flexattn_blockmask* bm, float scale,
+                     const flexattn_tensor* O, float* LSE, void* stream);
+
+/* ---- backward (backward template of section 4.1) -----------------------------------
+ * With P = softmax of the modified masked scores recomputed from LSE:
+ *   dV = P^T dO;  dP = dO V^T;  dS' = P * (dP - rowsum(dO * O));  dS = dS' * d score_mod/d s;
+ *   dQ = scale * dS K;  dK = scale * dS^T Q;  dK and dV are summed over the Hq / Hkv query
+ * heads that share a KV head.  Gradients with respect to captured buffers (alibi_bias,
+ * rel_bias) are not produced.  dQ [B,Hq,q_len,D], dK, dV [B,Hkv,kv_len,D] bf16.
+ *   ws     device workspace of at least flexattn_backward_workspace_bytes(dims) bytes.
+ */
+size_t flexattn_backward_workspace_bytes(const flexattn_dims* dims);
+int flexattn_backward(const flexattn_dims* dims,
+                      const flexattn_tensor* Q, const flexattn_tensor* K, const flexattn_tensor* V,
+                      const flexattn_tensor* O, const flexattn_tensor* dO, const float* LSE,
+                      uint32_t score_id, uint32_t mask_id, const flexattn_mod_params* params,
+                      const flexattn_blockmask* bm, float scale,
+                      const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---- paged attention (section 5.1) --------------------------------------------------
+ * BlockMask conversion: each of the first num_blocks[b,h,i] entries j of indices[b,h,i,:]
+ * (logical KV block numbers; Bk == page size) becomes page_table[b, j]; the tail stays 0 and
+ * the counts are unchanged.  phys2log (nullable, int32[n_pool_pages], pre-filled by the
+ * caller, e.g. with -1) receives phys2log[page_table[b, j]] = j for every converted entry:
+ * the vector that turns a physical KV index back into the logical one the user's mods expect.
+ *   num_blocks [Bm,Hm,NR], indices/phys_indices [Bm,Hm,NR,NC], page_table [Bm, pt_stride].
+ */
+int flexattn_paged_convert_blockmask(const int32_t* num_blocks, const int32_t* indices,
+                                     int32_t Bm, int32_t Hm, int32_t NR, int32_t NC,
+                                     const int32_t* page_table, int64_t pt_stride,
+                                     int32_t* phys_indices, int32_t* phys2log, int32_t n_pool_pages,
+                                     void* stream);
+
+/* Paged decode: one query token per sequence against a paged KV cache (decoding template of
+ * section 4.1 + fused indirect access of section 5.1), split over KV and combined.
+ *   Q       [nseq, Hq, D] bf16 (stride_q_seq elements between sequences, heads contiguous)
+ *   K_pool, V_pool  [n_pool_pages, Hkv, page_size, D] bf16, dense
+ *   page_table [nseq, pt_stride] int32: logical page j of sequence b lives in pool page
+ *              page_table[b, j]; only the first ceil(ctx_lens[b] / page_size) entries are read
+ *   ctx_lens   [nseq] int32: visible keys are kv_idx < ctx_lens[b] (0 is legal: O = 0,
+ *              LSE = -inf).  score_mods see q_idx = ctx_lens[b] - 1 and the LOGICAL kv_idx.
+ *   O [nseq, Hq, D] bf16 dense; LSE nullable [nseq, Hq] fp32.
+ * page_size must be 16, 32, 64 or 128; Hq / Hkv <= 16; mask_id must be FLEXATTN_MASK_CTX_LEN.
+ */
+typedef struct flexattn_decode_dims {
+    int32_t nseq, Hq, Hkv, D, page_size, max_pages, n_pool_pages;
+} flexattn_decode_dims;
+
+size_t flexattn_paged_decode_workspace_bytes(const flexattn_decode_dims* dims);
+int flexattn_paged_decode(const flexattn_decode_dims* dims,
+                          const void* Q, int64_t stride_q_seq,
+                          const void* K_pool, const void* V_pool,
+                          const int32_t* page_table, int64_t pt_stride, const int32_t* ctx_lens,
+                          uint32_t score_id, uint32_t mask_id, const flexattn_mod_params* params,
+                          float scale, void* O, float* LSE,
+                          void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXATTN_H */

@@ -1,0 +1,80 @@
+// flexattn_backward: argument validation, the delta pre-pass and dispatch to the compiled variant.
+#include "bwd_kernel.h"
+#include "variants.h"
+
+namespace flexattn {
+
+#define DECL(i) int bwd_launch_##i(const BwdArgs&, int, hipStream_t);
+DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8)
+#undef DECL
+typedef int (*BwdLauncher)(const BwdArgs&, int, hipStream_t);
+static const BwdLauncher kBwdLaunchers[kNumVariants] = {bwd_launch_0, bwd_launch_1, bwd_launch_2,
+                                                        bwd_launch_3, bwd_launch_4, bwd_launch_5,
+                                                        bwd_launch_6, bwd_launch_7, bwd_launch_8};
+int check_tensor(const flexattn_tensor* t);
+int check_problem(const flexattn_dims* d, const flexattn_blockmask* bm);
+
+}  // namespace flexattn
+
+using namespace flexattn;
+
+extern "C" size_t flexattn_backward_workspace_bytes(const flexattn_dims* d) {
+    if (!d || d->B <= 0 || d->Hq <= 0 || d->q_len <= 0) return 0;
+    return (size_t)2 * d->B * d->Hq * d->q_len * sizeof(float);
+}
+
+extern "C" int flexattn_backward(const flexattn_dims* dims, const flexattn_tensor* Q, const flexattn_tensor* K,
+                                 const flexattn_tensor* V, const flexattn_tensor* O, const flexattn_tensor* dO,
+                                 const float* LSE, uint32_t score_id, uint32_t mask_id,
+                                 const flexattn_mod_params* params, const flexattn_blockmask* bm, float scale,
+                                 const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
+                                 void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_problem(dims, bm);
+    if (rc != FLEXATTN_OK) return rc;
+    const flexattn_tensor* ts[] = {Q, K, V, O, dO, dQ, dK, dV};
+    for (const flexattn_tensor* t : ts)
+        if ((rc = check_tensor(t)) != FLEXATTN_OK) return rc;
+    if (!LSE || !ws || !(scale > 0.0f) || ((uintptr_t)ws & 15)) return FLEXATTN_ERR_INVALID_ARG;
+    if (!bm->q_num_blocks || !bm->q_indices || !bm->full_q_num_blocks || !bm->full_q_indices)
+        return FLEXATTN_ERR_INVALID_ARG;
+    if ((rc = check_mod_params(mask_id, score_id, params)) != FLEXATTN_OK) return rc;
+    const int vi = find_variant(mask_id, score_id);
+    if (vi < 0) return FLEXATTN_ERR_UNSUPPORTED;
+    if (ws_bytes < flexattn_backward_workspace_bytes(dims)) return FLEXATTN_ERR_WORKSPACE;
+
+    BwdArgs a = {};
+    a.Q = (const bf16*)Q->ptr; a.K = (const bf16*)K->ptr; a.V = (const bf16*)V->ptr;
+    a.O = (const bf16*)O->ptr; a.dO = (const bf16*)dO->ptr; a.LSE = LSE;
+    a.dQ = (bf16*)dQ->ptr; a.dK = (bf16*)dK->ptr; a.dV = (bf16*)dV->ptr;
+    const size_t rows = (size_t)dims->B * dims->Hq * dims->q_len;
+    a.delta = (float*)ws; a.lse2 = (float*)ws + rows;
+    a.q_sb = Q->stride_b; a.q_sh = Q->stride_h; a.q_ss = Q->stride_s;
+    a.k_sb = K->stride_b; a.k_sh = K->stride_h; a.k_ss = K->stride_s;
+    a.v_sb = V->stride_b; a.v_sh = V->stride_h; a.v_ss = V->stride_s;
+    a.o_sb = O->stride_b; a.o_sh = O->stride_h; a.o_ss = O->stride_s;
+    a.do_sb = dO->stride_b; a.do_sh = dO->stride_h; a.do_ss = dO->stride_s;
+    a.dq_sb = dQ->stride_b; a.dq_sh = dQ->stride_h; a.dq_ss = dQ->stride_s;
+    a.dk_sb = dK->stride_b; a.dk_sh = dK->stride_h; a.dk_ss = dK->stride_s;
+    a.dv_sb = dV->stride_b; a.dv_sh = dV->stride_h; a.dv_ss = dV->stride_s;
+    a.B = dims->B; a.Hq = dims->Hq; a.Hkv = dims->Hkv; a.G = dims->Hq / dims->Hkv;
+    a.q_len = dims->q_len; a.kv_len = dims->kv_len;
+    a.NR = dims->q_len / bm->Bq; a.NC = dims->kv_len / bm->Bk; a.Bq = bm->Bq; a.Bk = bm->Bk;
+    a.bm_Bm = bm->Bm; a.bm_Hm = bm->Hm;
+    a.kv_num = bm->kv_num_blocks; a.kv_idx = bm->kv_indices;
+    a.full_kv_num = bm->full_kv_num_blocks; a.full_kv_idx = bm->full_kv_indices;
+    a.q_num = bm->q_num_blocks; a.q_idx = bm->q_indices;
+    a.full_q_num = bm->full_q_num_blocks; a.full_q_idx = bm->full_q_indices;
+    a.scale = scale;
+    if (params) a.p = *params;
+
+    hipStream_t st = (hipStream_t)stream;
+    if (dims->D == 128) {
+        hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, a);
+    }
+    rc = kBwdLaunchers[vi](a, dims->D, st);
+    if (rc != FLEXATTN_OK) return rc;
+    FLEXATTN_HIP_TRY(hipGetLastError());
+    return FLEXATTN_OK;
+}

@@ -1,0 +1,198 @@
+// Shared device/host pieces of libflexattn (gfx950 only): vector types, MFMA wrappers,
+// the mask_mod / score_mod functors (paper sections 3.1 and 3.2) and host-side status helpers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "flexattn.h"
+
+namespace flexattn {
+
+typedef __bf16 bf16;
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// D[32x32] += A[32x16] * B[16x32], bf16 inputs, fp32 accumulate.
+// Operand layout (wave64): lane l supplies A[row = l % 32][k-slots of half l / 32] and
+// B[k-slots of half l / 32][col = l % 32], eight bf16 each; the k-slot <-> k mapping is the same
+// for A and B, so any consistent choice contracts correctly.
+// Result layout: register r of lane l holds D[row = 8 * (r / 4) + 4 * (l / 32) + r % 4][col = l % 32].
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row of the 32x32 result tile held in register r by a lane of half `half` (= lane / 32).
+__device__ __forceinline__ constexpr int crow(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Exchange a value with the lane 32 away (the other half of the wave).
+__device__ __forceinline__ float swap_halves(float v) { return __shfl_xor(v, 32, 64); }
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    bf16x2 v;
+    v[0] = (bf16)lo;
+    v[1] = (bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// ---------------------------------------------------------------------------------------
+// mask_mod: OR of up to two AND-terms over the primitive predicates.
+// A MaskRow caches what depends only on (b, h, q_idx); operator() takes kv_idx.
+// ---------------------------------------------------------------------------------------
+template <uint32_t TERM>
+struct MaskTermRow {
+    int q, window, prefix_len, doc_q, ctx;
+    const int32_t* doc_row;
+    __device__ __forceinline__ MaskTermRow(const flexattn_mod_params& p, int b, int /*h*/, int q_idx) {
+        q = q_idx;
+        window = p.window;
+        prefix_len = p.prefix_len;
+        doc_row = nullptr;
+        doc_q = 0;
+        ctx = 0;
+        if constexpr (TERM & FLEXATTN_M_DOCUMENT) {
+            doc_row = p.doc_ids + (int64_t)b * p.doc_stride_b;
+            doc_q = doc_row[q_idx];
+        }
+        if constexpr (TERM & FLEXATTN_M_CTX_LEN) ctx = p.ctx_lens[b];
+    }
+    __device__ __forceinline__ bool operator()(int kv) const {
+        bool r = true;
+        if constexpr (TERM & FLEXATTN_M_CAUSAL) r = r && (q >= kv);
+        if constexpr (TERM & FLEXATTN_M_SLIDING_WINDOW) r = r && (q - kv <= window);
+        if constexpr (TERM & FLEXATTN_M_DOCUMENT) r = r && (doc_row[kv] == doc_q);
+        if constexpr (TERM & FLEXATTN_M_PREFIX) r = r && (kv < prefix_len);
+        if constexpr (TERM & FLEXATTN_M_CTX_LEN) r = r && (kv < ctx);
+        return r;
+    }
+};
+
+template <uint32_t MASK>
+struct MaskRow {
+    static constexpr uint32_t T0 = MASK & 0xffu, T1 = (MASK >> 8) & 0xffu;
+    MaskTermRow<T0> t0;
+    MaskTermRow<T1> t1;
+    __device__ __forceinline__ MaskRow(const flexattn_mod_params& p, int b, int h, int q_idx)
+        : t0(p, b, h, q_idx), t1(p, b, h, q_idx) {}
+    __device__ __forceinline__ bool operator()(int kv) const {
+        bool r = t0(kv);
+        if constexpr (T1 != 0) r = r || t1(kv);
+        return r;
+    }
+};
+
+// ---------------------------------------------------------------------------------------
+// score_mod in the base-2 domain.  apply(acc, q - kv) returns log2(e) * score_mod(acc * scale),
+// so that exp(score') = exp2(apply(...)).  Order: ALiBi, relative bias, soft-cap.
+// dscore(x) is d score_mod / d s given x = apply(...), used by the backward pass.
+// ---------------------------------------------------------------------------------------
+template <uint32_t SCORE>
+struct ScoreMod {
+    static constexpr bool kAlibi = SCORE & FLEXATTN_SCORE_ALIBI;
+    static constexpr bool kRel = SCORE & FLEXATTN_SCORE_REL_BIAS;
+    static constexpr bool kCap = SCORE & FLEXATTN_SCORE_SOFTCAP;
+    float k_acc;      // multiplies the raw dot product
+    float k_bias;     // alibi_bias[h], pre-multiplied like k_acc
+    float k_tab;      // factor applied to table entries
+    float capl2;      // softcap * log2(e)
+    float inv_capl2;
+    const float* tab; // rel_bias row of head h
+    int rel_max;
+
+    __device__ __forceinline__ ScoreMod(const flexattn_mod_params& p, int h, float scale) {
+        float mul = kCap ? (2.0f * kLog2e / p.softcap) : kLog2e;   // soft-cap needs exp(2 s / cap)
+        k_acc = scale * mul;
+        k_bias = kAlibi ? p.alibi_bias[h] * mul : 0.0f;
+        k_tab = mul;
+        tab = kRel ? p.rel_bias + (int64_t)h * p.rel_len : nullptr;
+        rel_max = kRel ? p.rel_len - 1 : 0;
+        capl2 = kCap ? p.softcap * kLog2e : 0.0f;
+        inv_capl2 = kCap ? 1.0f / capl2 : 0.0f;
+    }
+
+    __device__ __forceinline__ float apply(float acc, int dq) const {
+        float y = acc * k_acc;
+        if constexpr (kAlibi) y = __builtin_fmaf(k_bias, (float)dq, y);
+        if constexpr (kRel) {
+            int r = dq < 0 ? 0 : (dq > rel_max ? rel_max : dq);
+            y = __builtin_fmaf(tab[r], k_tab, y);
+        }
+        if constexpr (kCap) {
+            // cap * tanh(s / cap) = cap * (1 - 2 / (1 + exp(2 s / cap)))
+            float e = fast_exp2(y);
+            y = __builtin_fmaf(-2.0f * capl2, fast_rcp(1.0f + e), capl2);
+        }
+        return y;
+    }
+
+    __device__ __forceinline__ float dscore(float x) const {
+        if constexpr (kCap) {
+            float t = x * inv_capl2;      // tanh(s / cap)
+            return 1.0f - t * t;
+        } else {
+            return 1.0f;
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------------------
+// host helpers
+// ---------------------------------------------------------------------------------------
+void set_last_hip_error(int e);
+
+#define FLEXATTN_HIP_TRY(expr)                          \
+    do {                                                \
+        hipError_t _e = (expr);                         \
+        if (_e != hipSuccess) {                         \
+            ::flexattn::set_last_hip_error((int)_e);    \
+            return FLEXATTN_ERR_HIP;                    \
+        }                                               \
+    } while (0)
+
+inline bool mask_id_valid(uint32_t m) {
+    return (m & ~0x1f1fu) == 0 && !((m & 0xffu) == 0 && (m >> 8) != 0);
+}
+inline bool score_id_valid(uint32_t s) { return (s & ~7u) == 0; }
+inline bool mask_uses(uint32_t m, uint32_t prim) { return ((m | (m >> 8)) & prim) != 0; }
+
+// Pointers the selected mods will dereference must be present.
+inline int check_mod_params(uint32_t mask_id, uint32_t score_id, const flexattn_mod_params* p) {
+    if (!mask_id_valid(mask_id) || !score_id_valid(score_id)) return FLEXATTN_ERR_INVALID_ARG;
+    bool need = mask_id != 0 || score_id != 0;
+    if (need && !p) return FLEXATTN_ERR_INVALID_ARG;
+    if (!p) return FLEXATTN_OK;
+    if (mask_uses(mask_id, FLEXATTN_M_DOCUMENT) && !p->doc_ids) return FLEXATTN_ERR_INVALID_ARG;
+    if (mask_uses(mask_id, FLEXATTN_M_CTX_LEN) && !p->ctx_lens) return FLEXATTN_ERR_INVALID_ARG;
+    if ((score_id & FLEXATTN_SCORE_ALIBI) && !p->alibi_bias) return FLEXATTN_ERR_INVALID_ARG;
+    if ((score_id & FLEXATTN_SCORE_REL_BIAS) && (!p->rel_bias || p->rel_len <= 0 || p->rel_len > 1024))
+        return FLEXATTN_ERR_INVALID_ARG;
+    if ((score_id & FLEXATTN_SCORE_SOFTCAP) && !(p->softcap > 0.0f)) return FLEXATTN_ERR_INVALID_ARG;
+    return FLEXATTN_OK;
+}
+
+// The (mask, score) pairs that forward/backward kernels are instantiated for.
+// X(mask_id, score_id)
+#define FLEXATTN_FOR_EACH_VARIANT(X)                                                    \
+    X(FLEXATTN_MASK_NONE, FLEXATTN_SCORE_IDENTITY)                                      \
+    X(FLEXATTN_MASK_CAUSAL, FLEXATTN_SCORE_IDENTITY)                                    \
+    X(FLEXATTN_MASK_CAUSAL, FLEXATTN_SCORE_ALIBI)                                       \
+    X(FLEXATTN_MASK_CAUSAL, FLEXATTN_SCORE_SOFTCAP)                                     \
+    X(FLEXATTN_MASK_SWA_CAUSAL, FLEXATTN_SCORE_IDENTITY)                                \
+    X(FLEXATTN_MASK_PREFIX_LM, FLEXATTN_SCORE_IDENTITY)                                 \
+    X(FLEXATTN_MASK_DOCUMENT_CAUSAL, FLEXATTN_SCORE_IDENTITY)                           \
+    X(FLEXATTN_MASK_DOCUMENT_CAUSAL, FLEXATTN_SCORE_ALIBI)                              \
+    X(FLEXATTN_MASK_SWA_CAUSAL_OR_PREFIX, FLEXATTN_SCORE_REL_BIAS)
+
+}  // namespace flexattn

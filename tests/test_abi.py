@@ -1,0 +1,92 @@
+"""The C-ABI library loads, exports every symbol include/flexattn.h declares, and rejects bad
+arguments on the host before anything touches a GPU (CPU only; no compute calls)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2412_05496_amd as fa
+from paper_2412_05496_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flexattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(flexattn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding._lib()
+    names = declared_symbols()
+    assert {"flexattn_blockmask_build", "flexattn_forward", "flexattn_backward", "flexattn_paged_decode",
+            "flexattn_paged_convert_blockmask"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror_and_version():
+    lib = binding._lib()
+    assert lib.flexattn_version() >= 100
+    assert lib.flexattn_strerror(0) == b"ok"
+    for st in (-1, -2, -3, -4):
+        assert lib.flexattn_strerror(st) not in (b"ok", b"unknown status")
+
+
+def test_supported_variants():
+    assert fa.flexattn_is_supported(fa.MASK_CAUSAL, fa.SCORE_SOFTCAP, 128)
+    assert fa.flexattn_is_supported(fa.MASK_DOCUMENT_CAUSAL, fa.SCORE_ALIBI, 64)
+    assert fa.flexattn_is_supported(fa.MASK_SWA_CAUSAL_OR_PREFIX, fa.SCORE_REL_BIAS, 128)
+    assert not fa.flexattn_is_supported(fa.MASK_CAUSAL, fa.SCORE_SOFTCAP, 96)
+    assert not fa.flexattn_is_supported(fa.MASK_CTX_LEN, fa.SCORE_REL_BIAS | fa.SCORE_SOFTCAP, 128)
+
+
+def test_null_and_bad_arguments_are_rejected_on_the_host():
+    lib = binding._lib()
+    assert lib.flexattn_forward(None, None, None, None, 0, 0, None, None, 1.0, None, None, None) == fa.ERR_INVALID_ARG
+    assert lib.flexattn_blockmask_build(0, None, None, None, None, 0, None) == fa.ERR_INVALID_ARG
+    assert lib.flexattn_paged_decode(None, None, 0, None, None, None, 0, None, 0, 0, None, 1.0, None, None, None, 0,
+                                     None) == fa.ERR_INVALID_ARG
+    d = binding._Dims(1, 3, 2, 128, 128, 128)           # Hq not a multiple of Hkv
+    bm = binding._BlockMask(1, 1, 128, 128, 64, 64, 1, 1, 1, 1, 1, 1, 1, 1)
+    assert lib.flexattn_forward(C.byref(d), None, None, None, 0, 0, None, C.byref(bm), 1.0, None, None,
+                                None) == fa.ERR_INVALID_ARG
+    d = binding._Dims(1, 2, 2, 128, 128, 96)            # head dimension not compiled in
+    assert lib.flexattn_forward(C.byref(d), None, None, None, 0, 0, None, C.byref(bm), 1.0, None, None,
+                                None) == fa.ERR_UNSUPPORTED
+    d = binding._Dims(1, 2, 2, 128, 128, 128)
+    bm = binding._BlockMask(1, 1, 128, 128, 32, 64, 1, 1, 1, 1, 1, 1, 1, 1)   # Bq = 32 unsupported
+    assert lib.flexattn_forward(C.byref(d), None, None, None, 0, 0, None, C.byref(bm), 1.0, None, None,
+                                None) == fa.ERR_UNSUPPORTED
+    # ragged sequence (q_len % Bq != 0) is refused by the builder
+    bm = binding._BlockMask(1, 1, 100, 128, 64, 64, 1, 1, 1, 1, 1, 1, 1, 1)
+    assert lib.flexattn_blockmask_build(fa.MASK_CAUSAL, None, C.byref(bm), None, 1, 1 << 20, None) == fa.ERR_INVALID_ARG
+    p = binding._ModParams()
+    assert lib.flexattn_blockmask_build(fa.MASK_CAUSAL, C.byref(p), C.byref(bm), None, 1, 1 << 20,
+                                        None) == fa.ERR_UNSUPPORTED
+    # document mask without doc_ids
+    bm = binding._BlockMask(1, 1, 128, 128, 64, 64, 1, 1, 1, 1, 1, 1, 1, 1)
+    assert lib.flexattn_blockmask_build(fa.MASK_DOCUMENT, C.byref(p), C.byref(bm), None, 1, 1 << 20,
+                                        None) == fa.ERR_INVALID_ARG
+    # workspace too small
+    assert lib.flexattn_blockmask_build(fa.MASK_CAUSAL, C.byref(p), C.byref(bm), None, 1, 1, None) == fa.ERR_WORKSPACE
+
+
+def test_workspace_queries():
+    assert fa.flexattn_blockmask_workspace_bytes(1, 1, 8192, 8192, 128, 64) >= 64 * 128
+    dd = binding._DecodeDims(64, 32, 8, 128, 16, 2048, 1000)
+    n = binding._lib().flexattn_paged_decode_workspace_bytes(C.byref(dd))
+    assert n >= 64 * 32 * 130 * 4 and n % 4 == 0
+    d = binding._Dims(4, 16, 16, 8192, 8192, 128)
+    assert binding._lib().flexattn_backward_workspace_bytes(C.byref(d)) == 2 * 4 * 16 * 8192 * 4
+
+
+def test_product_does_not_import_oracle():
+    pkg = os.path.join(ROOT, "paper_2412_05496_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.replace("no CPU fallback", ""), f

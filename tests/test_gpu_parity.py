@@ -1,0 +1,112 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on identical seeded inputs.
+
+BlockMask arrays must match bit for bit.  O (bf16) vs oracle: max abs <= 2e-2, mean abs <= 2e-3;
+LSE <= 1e-2; gradients: max abs <= 2e-2 * max(1, max|ref|), mean abs <= 2e-3 * max(1, 10 mean|ref|).
+"""
+import pytest
+import torch
+
+import flex_workloads as wlm
+from oracle import flex_oracle as fo
+
+from helpers import (assert_blockmask_equal, check_grad, check_output, library_mods, oracle_mods, run_backward,
+                     run_forward)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+# Scaled-down versions of the benchmark workloads that the oracle finishes in seconds; each spans
+# several BlockMask blocks per row, full + partial blocks and (for GQA) several heads per group.
+SMALL = {
+    "cfg1": wlm.CFG1,
+    "cfg2_small": wlm.CFG2.scaled(B=2, Hq=2, Hkv=2, S=1024),
+    "cfg3_small": wlm.CFG3.scaled(Hq=4, Hkv=4, S=2048, doc_len_min=100, doc_len_max=700),
+    "cfg4_small": wlm.CFG4.scaled(B=1, Hq=8, Hkv=2, S=2048, window=300, prefix_len=128, rel_len=256),
+    "noop_d64_64x64": wlm.Workload("noop", B=1, Hq=2, Hkv=2, S=512, D=64, Bq=64, Bk=64, mask="none",
+                                   score="identity", seed=11),
+    "causal_alibi_bk128": wlm.Workload("causal_alibi", B=1, Hq=4, Hkv=2, S=1024, D=128, Bq=64, Bk=128,
+                                       mask="causal", score="alibi", seed=12),
+    "swa_d64": wlm.Workload("swa", B=1, Hq=2, Hkv=1, S=1024, D=64, Bq=128, Bk=128, mask="swa_causal",
+                            score="identity", seed=13, window=200),
+    "prefix_lm_d128": wlm.Workload("prefix_lm", B=2, Hq=2, Hkv=2, S=768, D=128, Bq=128, Bk=64, mask="prefix_lm",
+                                   score="identity", seed=14, prefix_len=200),
+    "doc_causal_d128": wlm.Workload("doc", B=2, Hq=2, Hkv=1, S=1024, D=128, Bq=128, Bk=64, mask="doc_causal",
+                                    score="identity", seed=15, doc_len_min=50, doc_len_max=400),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_forward_backward_small(name):
+    wl = SMALL[name]
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    score, mask = oracle_mods(wl, inp)
+    print(f"[case] {name} {wl}", flush=True)
+    O, LSE, bm, ids = run_forward(wl, inp, DEV)
+    ref_bm = fo.create_block_mask(mask, bm.Bm, 1, wl.S, wl.S, wl.Bq, wl.Bk)
+    assert_blockmask_equal(bm, ref_bm)
+    O_ref, LSE_ref = fo.flex_attention(inp.Q, inp.K, inp.V, score, mask, inp.scale)
+    check_output(O, LSE, O_ref, LSE_ref)
+    dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids)
+    dQ_ref, dK_ref, dV_ref = fo.flex_attention_backward(inp.Q, inp.K, inp.V, inp.dO, score, mask, inp.scale)
+    check_grad("dQ", dQ, dQ_ref)
+    check_grad("dK", dK, dK_ref)
+    check_grad("dV", dV, dV_ref)
+
+
+def test_causal_row0_is_v0_bit_exact():
+    wl = wlm.CFG1
+    inp = wlm.make_train_inputs(wl)
+    O, LSE, _, _ = run_forward(wl, inp, DEV)
+    assert torch.equal(O[:, :, 0].cpu(), inp.V[:, :, 0])
+
+
+def test_all_masked_rows_give_zero_output_and_gradients():
+    # sliding window with a negative window hides every key: O = 0, LSE = -inf, zero gradients
+    wl = wlm.Workload("dead", B=1, Hq=2, Hkv=1, S=256, D=64, Bq=64, Bk=64, mask="swa_causal", score="identity",
+                      seed=21, window=-1)
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    O, LSE, bm, ids = run_forward(wl, inp, DEV)
+    assert int(bm.kv_num_blocks.sum()) == 0 and int(bm.full_kv_num_blocks.sum()) == 0
+    assert (O == 0).all() and torch.isinf(LSE).all() and (LSE < 0).all()
+    dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids)
+    assert (dQ == 0).all() and (dK == 0).all() and (dV == 0).all()
+
+
+def test_rows_dead_inside_live_blocks():
+    # document mask with every document alone except one: rows whose keys are all in *partial* blocks
+    # and a prefix-only mask where later columns have no visible query at all (dK = dV = 0 there)
+    wl = wlm.Workload("prefix_only", B=1, Hq=2, Hkv=2, S=512, D=64, Bq=64, Bk=64, mask="swa_causal_or_prefix",
+                      score="rel_bias", seed=22, window=-1, prefix_len=70, rel_len=16)
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    score, mask = oracle_mods(wl, inp)
+    O, LSE, bm, ids = run_forward(wl, inp, DEV)
+    assert_blockmask_equal(bm, fo.create_block_mask(mask, 1, 1, wl.S, wl.S, wl.Bq, wl.Bk))
+    O_ref, LSE_ref = fo.flex_attention(inp.Q, inp.K, inp.V, score, mask, inp.scale)
+    check_output(O, LSE, O_ref, LSE_ref)
+    dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids)
+    g_ref = fo.flex_attention_backward(inp.Q, inp.K, inp.V, inp.dO, score, mask, inp.scale)
+    for n, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), g_ref):
+        check_grad(n, g, r)
+    assert (dK[:, :, 70:] == 0).all() and (dV[:, :, 70:] == 0).all()
+
+
+def test_forward_is_deterministic_and_strided_inputs_work():
+    wl = SMALL["cfg2_small"]
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    O1, L1, bm, ids = run_forward(wl, inp, DEV)
+    O2, L2, _, _ = run_forward(wl, inp, DEV)
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    g1 = run_backward(wl, inp, DEV, O1, L1, bm, ids)
+    g2 = run_backward(wl, inp, DEV, O1, L1, bm, ids)
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)
+    # same data laid out [B, S, H, D] in memory, viewed as [B, H, S, D]
+    import paper_2412_05496_amd as fa
+    mask_id, score_id, params, Q, K, V = ids
+    Qs, Ks, Vs = (t.transpose(1, 2).contiguous().transpose(1, 2) for t in (Q, K, V))
+    assert Qs.stride(2) != Q.stride(2)
+    O3 = torch.empty_like(Qs)
+    L3 = torch.empty_like(L1)
+    fa.flexattn_forward(Qs, Ks, Vs, score_id, mask_id, params, bm, inp.scale, O3, L3)
+    torch.cuda.synchronize()
+    assert torch.equal(O3, O1) and torch.equal(L3, L1)
