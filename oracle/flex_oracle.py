@@ -250,21 +250,23 @@ def flex_attention(Q, K, V, score_mod: ScoreMod, mask_mod: MaskMod, scale: Optio
 # Backward
 # --------------------------------------------------------------------------
 def attention_head_backward(Qh, Kh, Vh, dOh, score_mod: ScoreMod, mask_mod: MaskMod, scale: float,
-                            b: int, h: int, stripe: int = 1024):
-    """One query head: dQ [Sq, D] and this head's contributions dK, dV [Skv, D] (fp64).
+                            b: int, h: int, q_rows: Optional[torch.Tensor] = None, stripe: int = 1024):
+    """One query head: dQ [rows, D] and this head's contributions dK, dV [Skv, D] (fp64).
 
     With P the softmax of the modified masked scores:
       dV = P^T dO;  dP = dO V^T;  delta = rowsum(P * dP);  dS' = P * (dP - delta);
       dS = dS' * (d score_mod / d s);  dQ = scale * dS K;  dK = scale * dS^T Q.
-    Masked entries have P = 0 and so contribute nothing.
+    Masked entries have P = 0 and so contribute nothing.  With `q_rows`, only those query rows
+    are evaluated: dQ holds exactly their rows, dK / dV only their contributions.
     """
     Qh, Kh, Vh, dOh = Qh.to(F64), Kh.to(F64), Vh.to(F64), dOh.to(F64)
-    Sq = Qh.shape[0]
-    dQ = torch.empty_like(Qh)
+    rows = _idx(0, Qh.shape[0]) if q_rows is None else q_rows.to(torch.int64)
+    dQ = torch.empty(rows.numel(), Qh.shape[1], dtype=F64)
     dK = torch.zeros_like(Kh)
     dV = torch.zeros_like(Vh)
-    for r0 in range(0, Sq, stripe):
-        q_idx = _idx(r0, min(r0 + stripe, Sq))
+    kv_idx = _idx(0, Kh.shape[0]).view(1, -1)
+    for r0 in range(0, rows.numel(), stripe):
+        q_idx = rows[r0:r0 + stripe]
         s, s_mod, keep = _modified_scores(Qh, Kh, score_mod, mask_mod, scale, b, h, q_idx)
         P, _ = _softmax_rows(s_mod, keep)
         dO_r = dOh[q_idx]
@@ -272,10 +274,9 @@ def attention_head_backward(Qh, Kh, Vh, dOh, score_mod: ScoreMod, mask_mod: Mask
         dP = dO_r @ Vh.T
         delta = (P * dP).sum(dim=1, keepdim=True)
         dS_mod = P * (dP - delta)
-        kv_idx = _idx(0, Kh.shape[0]).view(1, -1)
         g = score_mod.grad(s, b, h, q_idx.view(-1, 1), kv_idx)
         dS = torch.where(keep, dS_mod * g, torch.zeros_like(dS_mod))
-        dQ[q_idx] = scale * (dS @ Kh)
+        dQ[r0:r0 + stripe] = scale * (dS @ Kh)
         dK += scale * (dS.T @ Qh[q_idx])
     return dQ, dK, dV
 

@@ -121,3 +121,19 @@ def test_masked_keys_get_no_gradient():
     dQ, dK, dV = fo.flex_attention_backward(Q, K, V, dO, fo.Softcap(2.0), fo.prefix_mask(3))
     assert (dK[0, 0, 3:] == 0).all() and (dV[0, 0, 3:] == 0).all()
     assert dK[0, 0, :3].abs().min() > 0 and dV[0, 0, :3].abs().min() > 0
+
+
+def test_backward_row_subset_matches_full():
+    Q, K, V, dO = rand(1, 1, 40, 8, seed=1), rand(1, 1, 40, 8, seed=2), rand(1, 1, 40, 8, seed=3), rand(1, 1, 40, 8, seed=4)
+    args = (Q[0, 0], K[0, 0], V[0, 0], dO[0, 0], fo.Softcap(2.0), fo.causal_mask, 0.4, 0, 0)
+    dQ, dK, dV = fo.attention_head_backward(*args)
+    rows = torch.tensor([39, 3, 17])
+    dq, dk, dv = fo.attention_head_backward(*args, q_rows=rows)
+    assert torch.allclose(dq, dQ[rows], atol=1e-13, rtol=0)
+    # the remaining rows supply the rest of dK / dV
+    rest = torch.tensor([i for i in range(40) if i not in (39, 3, 17)])
+    _, dk2, dv2 = fo.attention_head_backward(*args, q_rows=rest, stripe=9)
+    assert torch.allclose(dk + dk2, dK, atol=1e-13, rtol=0) and torch.allclose(dv + dv2, dV, atol=1e-13, rtol=0)
+    # keys 30.. are seen only by rows 30.. under the causal mask
+    _, dk3, dv3 = fo.attention_head_backward(*args, q_rows=torch.arange(30, 40))
+    assert torch.allclose(dk3[30:], dK[30:], atol=1e-13, rtol=0) and torch.allclose(dv3[30:], dV[30:], atol=1e-13, rtol=0)
