@@ -1,0 +1,202 @@
+"""Benchmark of the FlexAttention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = BlockMask build + forward + backward (all three through the C ABI) on the dense
+causal + tanh-softcap training shape B=4, H=16, S=8192, D=128 (bf16, synthetic N(0,1) inputs
+resident in HBM).  `value` is TFLOP/s over UNMASKED FLOPs only: 4*D per unmasked (q, kv) pair for
+the forward, 10*D for the backward (five GEMMs; recomputation is not credited).
+
+The JSON line also carries
+  roofline      the longest kernel of the step against the dense bf16 MFMA peak, timed with
+                events on the launch stream;
+  decode        the paged split-KV decode workload (64 sequences, 16-token pages) in HBM GB/s of
+                algorithmic K+V bytes, with its own roofline object;
+  cpu_baseline  the fp64 oracle timed on this host's cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def event_time_ms(fn, iters: int) -> float:
+    """Average duration of fn() in ms, bracketed by events on the current (launch) stream."""
+    import torch
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=3, help="(b, h) slices the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import flex_workloads as wlm
+    import paper_2412_05496_amd as fa
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, W = args.steps, args.warmup
+
+    # ------------------------------------------------------------------ training shape
+    wl = wlm.CFG2
+    inp = wlm.make_train_inputs(wl)
+    Q, Kt, V, dO = (t.to(dev) for t in (inp.Q, inp.K, inp.V, inp.dO))
+    params = fa.ModParams(softcap=wl.softcap)
+    mask_id, score_id = fa.MASK_CAUSAL, fa.SCORE_SOFTCAP
+    bm = fa.alloc_blockmask(1, 1, wl.S, wl.S, wl.Bq, wl.Bk, device=dev)
+    bm_ws = torch.empty(fa.flexattn_blockmask_workspace_bytes(1, 1, wl.S, wl.S, wl.Bq, wl.Bk), dtype=torch.uint8,
+                        device=dev)
+    O = torch.empty_like(Q)
+    LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=dev)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Kt), torch.empty_like(V)
+    bwd_ws = torch.empty(fa.flexattn_backward_workspace_bytes(Q, Kt), dtype=torch.uint8, device=dev)
+
+    def build():
+        fa.flexattn_blockmask_build(mask_id, params, bm, bm_ws)
+
+    def fwd():
+        fa.flexattn_forward(Q, Kt, V, score_id, mask_id, params, bm, inp.scale, O, LSE)
+
+    def bwd(stages=fa.BWD_ALL):
+        fa.flexattn_backward_stages(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV,
+                                    bwd_ws, stages)
+
+    def step():
+        build()
+        fwd()
+        bwd()
+
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / K
+
+    pairs = wl.B * wl.Hq * wl.S * (wl.S + 1) // 2
+    stats = bm.stats.cpu().tolist()
+    assert stats[3] * wl.B * wl.Hq == pairs, "BlockMask unmasked-pair count disagrees with the closed form"
+    flops_fwd, flops_bwd = 4 * wl.D * pairs, 10 * wl.D * pairs
+    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel durations (events on the launch stream)
+    kt = {
+        "blockmask_build": event_time_ms(build, K),
+        "fwd": event_time_ms(fwd, K),
+        "bwd_delta": event_time_ms(lambda: bwd(fa.BWD_DELTA), K),
+        "bwd_dkdv": event_time_ms(lambda: bwd(fa.BWD_DKDV), K),
+        "bwd_dq": event_time_ms(lambda: bwd(fa.BWD_DQ), K),
+    }
+    # algorithmic FLOPs per launch: forward 4*D*pairs; the backward's 10*D*pairs is split between
+    # its two MFMA kernels in proportion to the GEMMs each must execute (dK/dV: 4 of 7, dQ: 3 of 7)
+    alg = {"fwd": flops_fwd, "bwd_dkdv": flops_bwd * 4 / 7, "bwd_dq": flops_bwd * 3 / 7}
+    dom = max(alg, key=lambda k: kt[k])
+    achieved = alg[dom] / (kt[dom] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_ms": round(kt[dom], 4)}
+    bwd_ms = kt["bwd_delta"] + kt["bwd_dkdv"] + kt["bwd_dq"]
+    out = {
+        "metric": "flex_attention fwd+bwd TFLOP/s (unmasked FLOPs), dense causal + softcap",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "H": wl.Hq, "S": wl.S, "D": wl.D, "mask": "causal",
+                   "score_mod": "tanh softcap 30", "block": f"{wl.Bq}x{wl.Bk}",
+                   "step": "blockmask_build + forward + backward"},
+        "fwd_tflops": round(flops_fwd / (kt["fwd"] * 1e-3) / 1e12, 2),
+        "fwd_frac_of_bf16_peak": round(flops_fwd / (kt["fwd"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "bwd_tflops": round(flops_bwd / (bwd_ms * 1e-3) / 1e12, 2),
+        "bwd_frac_of_bf16_peak": round(flops_bwd / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "kernel_ms": {k: round(v, 4) for k, v in kt.items()},
+        "blockmask": {"partial": stats[0], "full": stats[1], "total": stats[2]},
+        "roofline": roofline,
+    }
+
+    # ------------------------------------------------------------------ paged decode
+    if not args.no_decode:
+        dwl = wlm.CFG5
+        dinp = wlm.make_decode_inputs(dwl)
+        dQ_, Kp, Vp = dinp.Q.to(dev), dinp.K_pool.to(dev), dinp.V_pool.to(dev)
+        pt, ctx = dinp.page_table.to(dev), dinp.ctx_lens.to(dev)
+        dO_ = torch.empty(dwl.B, dwl.Hq, dwl.D, dtype=torch.bfloat16, device=dev)
+        dL = torch.empty(dwl.B, dwl.Hq, dtype=torch.float32, device=dev)
+        dws = torch.empty(fa.flexattn_paged_decode_workspace_bytes(dQ_, Kp, pt), dtype=torch.uint8, device=dev)
+        dparams = fa.ModParams()
+
+        def dec():
+            fa.flexattn_paged_decode(dQ_, Kp, Vp, pt, ctx, fa.SCORE_IDENTITY, fa.MASK_CTX_LEN, dparams, dinp.scale,
+                                     dO_, dL, dws)
+
+        for _ in range(W):
+            dec()
+        torch.cuda.synchronize()
+        dms = event_time_ms(dec, K)
+        tokens = int(dinp.ctx_lens.sum())
+        alg_bytes = tokens * dwl.Hkv * dwl.D * 2 * 2          # K and V, bf16
+        gbs = alg_bytes / (dms * 1e-3) / 1e9
+        out["decode"] = {
+            "workload": dwl.name, "ms": round(dms, 4), "tokens": tokens, "algorithmic_bytes": alg_bytes,
+            "value": round(gbs, 1), "unit": "GB/s",
+            "roofline": {"kernel": "decode_split+combine", "bound": "hbm", "achieved": round(gbs, 1),
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                         "traffic": None},
+        }
+        del Kp, Vp
+
+    # ------------------------------------------------------------------ oracle on the host cores
+    if not args.no_cpu_baseline:
+        from oracle import flex_oracle as fo
+        heads = [(b, h) for b in range(wl.B) for h in range(wl.Hq)][:: max(1, wl.B * wl.Hq // args.cpu_heads)]
+        heads = heads[:args.cpu_heads]
+        score_mod, mask_mod = fo.Softcap(wl.softcap), fo.causal_mask
+        t0 = time.perf_counter()
+        for b, h in heads:
+            fo.attention_head(inp.Q[b, h], inp.K[b, h], inp.V[b, h], score_mod, mask_mod, inp.scale, b, h)
+            fo.attention_head_backward(inp.Q[b, h], inp.K[b, h], inp.V[b, h], inp.dO[b, h], score_mod, mask_mod,
+                                       inp.scale, b, h)
+        cpu_s = time.perf_counter() - t0
+        head_flops = 14 * wl.D * (wl.S * (wl.S + 1) // 2)
+        out["cpu_baseline"] = {
+            "value": round(len(heads) * head_flops / cpu_s / 1e12, 5), "unit": "TFLOP/s",
+            "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"fp64 oracle forward+backward of {len(heads)} of {wl.B * wl.Hq} (b, h) slices of {wl.name} "
+                      f"in {cpu_s:.1f} s (same unmasked-FLOP convention)",
+        }
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -183,6 +183,24 @@ int flexattn_backward(const flexattn_dims* dims,
                       const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* The same computation by stage, for callers that need only part of the gradients (frozen K/V:
+ * DQ only; frozen Q: DKDV only) or that time the stages separately.  DELTA fills the workspace
+ * from (O, dO, LSE) and must have run on the same workspace before DKDV or DQ; DKDV writes dK
+ * and dV; DQ writes dQ.  Output tensors of stages that are not selected may be NULL.
+ * flexattn_backward() is flexattn_backward_stages(..., FLEXATTN_BWD_ALL).
+ */
+#define FLEXATTN_BWD_DELTA 1u
+#define FLEXATTN_BWD_DKDV  2u
+#define FLEXATTN_BWD_DQ    4u
+#define FLEXATTN_BWD_ALL   7u
+int flexattn_backward_stages(const flexattn_dims* dims,
+                             const flexattn_tensor* Q, const flexattn_tensor* K, const flexattn_tensor* V,
+                             const flexattn_tensor* O, const flexattn_tensor* dO, const float* LSE,
+                             uint32_t score_id, uint32_t mask_id, const flexattn_mod_params* params,
+                             const flexattn_blockmask* bm, float scale,
+                             const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
+                             void* ws, size_t ws_bytes, void* stream, uint32_t stages);
+
 /* ---- paged attention (section 5.1) --------------------------------------------------
  * BlockMask conversion: each of the first num_blocks[b,h,i] entries j of indices[b,h,i,:]
  * (logical KV block numbers; Bk == page size) becomes page_table[b, j]; the tail stays 0 and

@@ -109,6 +109,8 @@ def _lib():
     lib.flexattn_backward.argtypes = [P(_Dims), P(_Tensor), P(_Tensor), P(_Tensor), P(_Tensor), P(_Tensor),
                                       C.c_void_p, C.c_uint32, C.c_uint32, P(_ModParams), P(_BlockMask), C.c_float,
                                       P(_Tensor), P(_Tensor), P(_Tensor), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.flexattn_backward_stages.restype = C.c_int
+    lib.flexattn_backward_stages.argtypes = lib.flexattn_backward.argtypes + [C.c_uint32]
     lib.flexattn_paged_convert_blockmask.restype = C.c_int
     lib.flexattn_paged_convert_blockmask.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                                      C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -263,6 +265,22 @@ def flexattn_backward(Q, K, V, O, dO, LSE, score_id: int, mask_id: int, params: 
     _check(_lib().flexattn_backward(C.byref(d), *(C.byref(t) for t in ts[:5]), LSE.data_ptr(), score_id, mask_id,
                                     C.byref(p), C.byref(c), scale, *(C.byref(t) for t in ts[5:]),
                                     ws.data_ptr(), ws.numel(), _stream()), "flexattn_backward")
+    return dQ, dK, dV
+
+
+BWD_DELTA, BWD_DKDV, BWD_DQ, BWD_ALL = 1, 2, 4, 7
+
+
+def flexattn_backward_stages(Q, K, V, O, dO, LSE, score_id: int, mask_id: int, params: ModParams, bm: BlockMask,
+                             scale: float, dQ, dK, dV, ws: torch.Tensor, stages: int):
+    """dQ / dK / dV may be None for stages that are not selected; `ws` must persist between stages."""
+    d, p, c = _dims(Q, K), params._c(), bm._c()
+    ins = [_tensor(t) for t in (Q, K, V, O, dO)]
+    outs = [None if t is None else _tensor(t) for t in (dQ, dK, dV)]
+    _check(_lib().flexattn_backward_stages(C.byref(d), *(C.byref(t) for t in ins), LSE.data_ptr(), score_id, mask_id,
+                                           C.byref(p), C.byref(c), scale,
+                                           *(None if t is None else C.byref(t) for t in outs),
+                                           ws.data_ptr(), ws.numel(), _stream(), stages), "flexattn_backward_stages")
     return dQ, dK, dV
 
 

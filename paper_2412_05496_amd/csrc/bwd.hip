@@ -4,10 +4,10 @@
 
 namespace flexattn {
 
-#define DECL(i) int bwd_launch_##i(const BwdArgs&, int, hipStream_t);
+#define DECL(i) int bwd_launch_##i(const BwdArgs&, int, uint32_t, hipStream_t);
 DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8)
 #undef DECL
-typedef int (*BwdLauncher)(const BwdArgs&, int, hipStream_t);
+typedef int (*BwdLauncher)(const BwdArgs&, int, uint32_t, hipStream_t);
 static const BwdLauncher kBwdLaunchers[kNumVariants] = {bwd_launch_0, bwd_launch_1, bwd_launch_2,
                                                         bwd_launch_3, bwd_launch_4, bwd_launch_5,
                                                         bwd_launch_6, bwd_launch_7, bwd_launch_8};
@@ -23,17 +23,25 @@ extern "C" size_t flexattn_backward_workspace_bytes(const flexattn_dims* d) {
     return (size_t)2 * d->B * d->Hq * d->q_len * sizeof(float);
 }
 
-extern "C" int flexattn_backward(const flexattn_dims* dims, const flexattn_tensor* Q, const flexattn_tensor* K,
-                                 const flexattn_tensor* V, const flexattn_tensor* O, const flexattn_tensor* dO,
-                                 const float* LSE, uint32_t score_id, uint32_t mask_id,
-                                 const flexattn_mod_params* params, const flexattn_blockmask* bm, float scale,
-                                 const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
-                                 void* ws, size_t ws_bytes, void* stream) {
+extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexattn_tensor* Q,
+                                        const flexattn_tensor* K, const flexattn_tensor* V, const flexattn_tensor* O,
+                                        const flexattn_tensor* dO, const float* LSE, uint32_t score_id,
+                                        uint32_t mask_id, const flexattn_mod_params* params,
+                                        const flexattn_blockmask* bm, float scale, const flexattn_tensor* dQ,
+                                        const flexattn_tensor* dK, const flexattn_tensor* dV, void* ws,
+                                        size_t ws_bytes, void* stream, uint32_t stages) {
     int rc = check_problem(dims, bm);
     if (rc != FLEXATTN_OK) return rc;
-    const flexattn_tensor* ts[] = {Q, K, V, O, dO, dQ, dK, dV};
+    if (stages == 0 || (stages & ~FLEXATTN_BWD_ALL)) return FLEXATTN_ERR_INVALID_ARG;
+    const flexattn_tensor* ts[] = {Q, K, V, O, dO};
     for (const flexattn_tensor* t : ts)
         if ((rc = check_tensor(t)) != FLEXATTN_OK) return rc;
+    if ((stages & FLEXATTN_BWD_DQ) && (rc = check_tensor(dQ)) != FLEXATTN_OK) return rc;
+    if ((stages & FLEXATTN_BWD_DKDV) && ((rc = check_tensor(dK)) != FLEXATTN_OK || (rc = check_tensor(dV)) != FLEXATTN_OK))
+        return rc;
+    static const flexattn_tensor kNoTensor = {nullptr, 0, 0, 0};
+    if (!(stages & FLEXATTN_BWD_DQ)) dQ = &kNoTensor;
+    if (!(stages & FLEXATTN_BWD_DKDV)) dK = dV = &kNoTensor;
     if (!LSE || !ws || !(scale > 0.0f) || ((uintptr_t)ws & 15)) return FLEXATTN_ERR_INVALID_ARG;
     if (!bm->q_num_blocks || !bm->q_indices || !bm->full_q_num_blocks || !bm->full_q_indices)
         return FLEXATTN_ERR_INVALID_ARG;
@@ -68,13 +76,27 @@ extern "C" int flexattn_backward(const flexattn_dims* dims, const flexattn_tenso
     if (params) a.p = *params;
 
     hipStream_t st = (hipStream_t)stream;
-    if (dims->D == 128) {
-        hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
-    } else {
-        hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, a);
+    if (stages & FLEXATTN_BWD_DELTA) {
+        if (dims->D == 128) {
+            hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
+        } else {
+            hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, a);
+        }
     }
-    rc = kBwdLaunchers[vi](a, dims->D, st);
-    if (rc != FLEXATTN_OK) return rc;
+    if (stages & (FLEXATTN_BWD_DKDV | FLEXATTN_BWD_DQ)) {
+        rc = kBwdLaunchers[vi](a, dims->D, stages, st);
+        if (rc != FLEXATTN_OK) return rc;
+    }
     FLEXATTN_HIP_TRY(hipGetLastError());
     return FLEXATTN_OK;
+}
+
+extern "C" int flexattn_backward(const flexattn_dims* dims, const flexattn_tensor* Q, const flexattn_tensor* K,
+                                 const flexattn_tensor* V, const flexattn_tensor* O, const flexattn_tensor* dO,
+                                 const float* LSE, uint32_t score_id, uint32_t mask_id,
+                                 const flexattn_mod_params* params, const flexattn_blockmask* bm, float scale,
+                                 const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
+                                 void* ws, size_t ws_bytes, void* stream) {
+    return flexattn_backward_stages(dims, Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, scale, dQ, dK, dV, ws,
+                                    ws_bytes, stream, FLEXATTN_BWD_ALL);
 }

@@ -7,7 +7,7 @@
 #endif
 
 namespace flexattn {
-int FLEXATTN_CAT(bwd_launch_, FLEXATTN_VARIANT)(const BwdArgs& a, int D, hipStream_t st) {
-    return launch_bwd_variant<kVariants[FLEXATTN_VARIANT].mask, kVariants[FLEXATTN_VARIANT].score>(a, D, st);
+int FLEXATTN_CAT(bwd_launch_, FLEXATTN_VARIANT)(const BwdArgs& a, int D, uint32_t stages, hipStream_t st) {
+    return launch_bwd_variant<kVariants[FLEXATTN_VARIANT].mask, kVariants[FLEXATTN_VARIANT].score>(a, D, stages, st);
 }
 }  // namespace flexattn

@@ -499,18 +499,19 @@ __global__ __launch_bounds__(NW * 64, 1) void bwd_dq_kernel(const BwdArgs a) {
 }
 
 template <uint32_t MASK, uint32_t SCORE>
-int launch_bwd_variant(const BwdArgs& a, int D, hipStream_t st) {
+int launch_bwd_variant(const BwdArgs& a, int D, uint32_t stages, hipStream_t st) {
     const int units = a.B * a.Hkv;
     const unsigned grid_kv = (unsigned)(((units + 7) / 8) * 8 * (a.kv_len / 64));
     const unsigned grid_q = (unsigned)(((units + 7) / 8) * 8 * a.G * a.NR);
+    const bool kv = stages & FLEXATTN_BWD_DKDV, q = stages & FLEXATTN_BWD_DQ;
     if (D == 128) {
-        hipLaunchKernelGGL((bwd_dkdv_kernel<128, MASK, SCORE>), dim3(grid_kv), dim3(256), 0, st, a);
-        if (a.Bq == 128) hipLaunchKernelGGL((bwd_dq_kernel<128, 4, MASK, SCORE>), dim3(grid_q), dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((bwd_dq_kernel<128, 2, MASK, SCORE>), dim3(grid_q), dim3(128), 0, st, a);
+        if (kv) hipLaunchKernelGGL((bwd_dkdv_kernel<128, MASK, SCORE>), dim3(grid_kv), dim3(256), 0, st, a);
+        if (q && a.Bq == 128) hipLaunchKernelGGL((bwd_dq_kernel<128, 4, MASK, SCORE>), dim3(grid_q), dim3(256), 0, st, a);
+        if (q && a.Bq == 64) hipLaunchKernelGGL((bwd_dq_kernel<128, 2, MASK, SCORE>), dim3(grid_q), dim3(128), 0, st, a);
     } else {
-        hipLaunchKernelGGL((bwd_dkdv_kernel<64, MASK, SCORE>), dim3(grid_kv), dim3(256), 0, st, a);
-        if (a.Bq == 128) hipLaunchKernelGGL((bwd_dq_kernel<64, 4, MASK, SCORE>), dim3(grid_q), dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((bwd_dq_kernel<64, 2, MASK, SCORE>), dim3(grid_q), dim3(128), 0, st, a);
+        if (kv) hipLaunchKernelGGL((bwd_dkdv_kernel<64, MASK, SCORE>), dim3(grid_kv), dim3(256), 0, st, a);
+        if (q && a.Bq == 128) hipLaunchKernelGGL((bwd_dq_kernel<64, 4, MASK, SCORE>), dim3(grid_q), dim3(256), 0, st, a);
+        if (q && a.Bq == 64) hipLaunchKernelGGL((bwd_dq_kernel<64, 2, MASK, SCORE>), dim3(grid_q), dim3(128), 0, st, a);
     }
     return FLEXATTN_OK;
 }
