@@ -122,20 +122,34 @@ struct ScoreMod {
         inv_capl2 = kCap ? 1.0f / capl2 : 0.0f;
     }
 
-    __device__ __forceinline__ float apply(float acc, int dq) const {
+    // Scaled score plus the additive biases, times the factor the following exp2 needs.
+    __device__ __forceinline__ float pre(float acc, int dq) const {
         float y = acc * k_acc;
         if constexpr (kAlibi) y = __builtin_fmaf(k_bias, (float)dq, y);
         if constexpr (kRel) {
             int r = dq < 0 ? 0 : (dq > rel_max ? rel_max : dq);
             y = __builtin_fmaf(tab[r], k_tab, y);
         }
-        if constexpr (kCap) {
-            // cap * tanh(s / cap) = cap * (1 - 2 / (1 + exp(2 s / cap)))
-            float e = fast_exp2(y);
-            y = __builtin_fmaf(-2.0f * capl2, fast_rcp(1.0f + e), capl2);
-        }
         return y;
     }
+
+    // Soft-cap only: r = 1 / (1 + exp(2 s / cap)), so that cap * tanh(s / cap) = cap * (1 - 2 r).
+    __device__ __forceinline__ float cap_r(float acc, int dq) const {
+        return fast_rcp(1.0f + fast_exp2(pre(acc, dq)));
+    }
+
+    __device__ __forceinline__ float apply(float acc, int dq) const {
+        if constexpr (kCap) {
+            return __builtin_fmaf(-2.0f * capl2, cap_r(acc, dq), capl2);
+        } else {
+            return pre(acc, dq);
+        }
+    }
+
+    // A soft-capped score never exceeds the cap, so softmax can use the cap itself as its
+    // (fixed) maximum when 2^(-2 cap log2 e) is still far from fp32 underflow: no running max,
+    // no rescaling, and p = exp2(-2 capl2 r) directly.
+    __device__ __forceinline__ bool bounded() const { return kCap && 2.0f * capl2 <= 100.0f; }
 
     __device__ __forceinline__ float dscore(float x) const {
         if constexpr (kCap) {

@@ -1,17 +1,24 @@
 // FlexAttention forward kernel for gfx950 (paper Eq. 1; forward template of section 4.1; block
 // skipping, full/partial split and indirect KV-block access of section 4.2; the KV prefetch of
-// the "Data Prefetching Pipeline" paragraph is the register-staged double buffer below).
+// the "Data Prefetching Pipeline" paragraph is the two-deep asynchronous LDS pipeline below).
 //
 // One workgroup owns one row of BlockMask blocks (Bq = NW * 32 query rows of one (b, hq)); each
 // wave owns 32 of those rows.  The score tile is computed TRANSPOSED, S^T = K Q^T, so that in the
 // MFMA result layout every lane holds scores of ONE query (column l % 32) and 16 keys per 32-key
 // block in its registers: the row max / row sum of the online softmax are in-register reductions
 // plus one exchange between the two halves of the wave, and P^T is already laid out as the B
-// operand of O^T += V^T P^T.  K tiles sit in LDS row-major (A operand of K Q^T), V tiles are
-// transposed on their way into LDS (A operand V^T), Q lives in registers for the whole kernel.
+// operand of O^T += V^T P^T.  K and V tiles go from global memory straight into LDS; K rows are
+// the A operand of K Q^T as they are, V^T fragments come out of the row-major V tile through the
+// transposing LDS read.  Q lives in registers for the whole kernel.
+//
+// Software pipeline, one barrier per tile: while the VALU works on the softmax of tile t, the
+// MFMA unit computes S^T of tile t+1; K(t+2) and V(t+1) are in flight from HBM/L2 meanwhile.
 #pragma once
 
+#include <type_traits>
+
 #include "flex_common.h"
+#include "lds_tiles.h"
 
 namespace flexattn {
 
@@ -35,25 +42,14 @@ struct FwdArgs {
 
 constexpr int kTileKV = 64;   // keys per kernel tile
 
-// Position inside a 16-key chunk of V^T rows at which key t (0..15) is stored, chosen so that the
-// eight keys a lane of half h needs for one MFMA (t = 4h + 8 * (j / 4) + j % 4, j = 0..7: the keys
-// its P^T registers hold) are contiguous: pos = 8 h + j.
-__device__ __forceinline__ constexpr int vt_pos16(int t) { return 8 * ((t >> 2) & 1) + 4 * (t >> 3) + (t & 3); }
-
-template <int D, int NW, uint32_t MASK, uint32_t SCORE>
+// BOUNDED: the score_mod ends in a soft-cap small enough that the cap itself serves as the fixed
+// softmax maximum (see ScoreMod::bounded); chosen by the host from the cap value.
+template <int D, int NW, uint32_t MASK, uint32_t SCORE, bool BOUNDED>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
-    constexpr int NT = NW * 64;
     constexpr int Bq = NW * 32;
-    constexpr int DC = D / 8;                      // 16-byte chunks per row
-    constexpr int KS = D + 8;                      // K row stride in LDS (elements), padded
-    constexpr int VS = kTileKV + 8;                // V^T row stride in LDS (elements), padded
-    constexpr int NKC = kTileKV * DC / NT;         // K chunks per thread
-    constexpr int NVU = (kTileKV / 4) * DC;        // V units (4 keys x 8 dims) per tile
-    constexpr int NVT = (NVU + NT - 1) / NT;       // V units per thread
-    static_assert(kTileKV * DC % NT == 0, "K tile must split evenly over the threads");
+    constexpr int TILE = kTileKV * D;              // elements per LDS tile
 
-    __shared__ __attribute__((aligned(16))) bf16 Ks[2][kTileKV * KS];
-    __shared__ __attribute__((aligned(16))) bf16 Vt[2][D * VS];
+    __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];   // K(even), K(odd), V(even), V(odd)
 
     // ---- workgroup -> (b, hkv, g, row of blocks).  Consecutive workgroup ids go to the 8 XCDs in
     // turn; all rows and all G query heads of one (b, hkv) are sent to the same XCD so that its K/V
@@ -98,59 +94,30 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
 
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
     const MaskRow<MASK> mrow(a.p, b, hq, q_row);
-
-    bf16x8 kreg[NKC];
-    u32x4 vreg[NVT][4];
+    const float neg2c = -2.0f * smod.capl2;
 
     auto tile_kv0 = [&](int t) {
         const int pos = t / a.sub, s = t - pos * a.sub;
         const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
         return blk * a.Bk + s * kTileKV;
     };
-    auto gload = [&](int kv0) {
-        const bf16* kp = k_base + (int64_t)kv0 * a.k_ss;
-        const bf16* vp = v_base + (int64_t)kv0 * a.v_ss;
+    const TileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
+    auto load_k = [&](int t) { k_loader.start(smem + (t & 1) * TILE, k_base + (int64_t)tile_kv0(t) * a.k_ss); };
+    auto load_v = [&](int t) { v_loader.start(smem + (2 + (t & 1)) * TILE, v_base + (int64_t)tile_kv0(t) * a.v_ss); };
+    const RowReader<D> k_reader(l32, half);
+    const TrReader<D> v_reader(lane);
+    const uint32_t smem_bytes = lds_addr(smem);
+
+    // S^T = K Q^T for the two 32-key blocks of the K tile in buffer BUF (compile-time)
+    auto qk = [&](auto buf_tag, f32x16 (&s)[2]) {
+        constexpr int BUF = decltype(buf_tag)::value;
 #pragma unroll
-        for (int i = 0; i < NKC; ++i) {
-            const int c = tid + i * NT, r = c / DC, cc = c % DC;
-            kreg[i] = *(const bf16x8*)(kp + (int64_t)r * a.k_ss + cc * 8);
-        }
+        for (int kvb = 0; kvb < 2; ++kvb) {
 #pragma unroll
-        for (int i = 0; i < NVT; ++i) {
-            const int u = tid + i * NT;
-            if (NVU % NT == 0 || u < NVU) {
-                const int gq = u / DC, cc = u % DC;
+            for (int r = 0; r < 16; ++r) s[kvb][r] = 0.0f;
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4)
-                    vreg[i][r4] = *(const u32x4*)(vp + (int64_t)(4 * gq + r4) * a.v_ss + cc * 8);
-            }
-        }
-    };
-    auto sstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < NKC; ++i) {
-            const int c = tid + i * NT, r = c / DC, cc = c % DC;
-            *(bf16x8*)(&Ks[buf][r * KS + cc * 8]) = kreg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < NVT; ++i) {
-            const int u = tid + i * NT;
-            if (NVU % NT == 0 || u < NVU) {
-                const int gq = u / DC, cc = u % DC;
-                const int pos = 16 * (gq >> 2) + vt_pos16(4 * (gq & 3));
-                // 4 keys x 8 dims -> 8 dims x 4 keys
-#pragma unroll
-                for (int wd = 0; wd < 4; ++wd) {
-                    const uint32_t r0 = vreg[i][0][wd], r1 = vreg[i][1][wd], r2 = vreg[i][2][wd], r3 = vreg[i][3][wd];
-                    u32x2 lo, hi;
-                    lo[0] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);
-                    lo[1] = __builtin_amdgcn_perm(r3, r2, 0x05040100u);
-                    hi[0] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);
-                    hi[1] = __builtin_amdgcn_perm(r3, r2, 0x07060302u);
-                    *(u32x2*)(&Vt[buf][(cc * 8 + 2 * wd) * VS + pos]) = lo;
-                    *(u32x2*)(&Vt[buf][(cc * 8 + 2 * wd + 1) * VS + pos]) = hi;
-                }
-            }
+            for (int ks = 0; ks < D / 16; ++ks)
+                s[kvb] = mfma32(k_reader.read(smem_bytes + BUF * (TILE * 2), kvb * 32, ks), qf[ks], s[kvb]);
         }
     };
 
@@ -159,104 +126,121 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+    // base-2 running max and this lane's part of the running sum; with a bounded soft-cap the
+    // maximum is fixed at the cap from the start
+    float m_run = BOUNDED ? smod.capl2 : -INFINITY, l_run = 0.0f;
 
-    int kv0 = tile_kv0(0);
-    gload(kv0);
-    sstore(0);
-    __syncthreads();
-
-    for (int t = 0; t < T; ++t) {
-        const int buf = t & 1;
-        int kv0_next = 0;
-        if (t + 1 < T) {
-            kv0_next = tile_kv0(t + 1);
-            gload(kv0_next);
-        }
-        const bool partial = (t / a.sub) >= n_full;
-
-        // ---- S^T = K Q^T : two 32-key blocks
-        f32x16 sacc[2];
+    // score_mod, mask_mod (partial blocks only) and softmax of one 32-key block whose first key is
+    // kvs: s -> P^T as two bf16 fragments.  The mask is a separate, rarely taken pass (kept a real
+    // branch) so that the common path is one straight run of VALU work next to the MFMAs around it.
+    auto softmax = [&](f32x16& s, int kvs, bool partial, bf16x8 (&pf)[2]) {
+        const int dq_base = q_row - kvs;
+        if constexpr (BOUNDED) {
+            // p = 2^(x - cap log2 e) = 2^(-2 cap log2 e * r): no maximum to track
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb) {
+            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(neg2c * smod.cap_r(s[r], dq_base - crow(r, half)));
+            if (partial) {
+                asm volatile("" ::: "memory");   // keep this a branch, not 16 selects on every tile
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kvb][r] = 0.0f;
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                const bf16x8 kf = *(const bf16x8*)(&Ks[buf][(kvb * 32 + l32) * KS + ks * 16 + half * 8]);
-                sacc[kvb] = mfma32(kf, qf[ks], sacc[kvb]);
+                for (int r = 0; r < 16; ++r) s[r] = mrow(kvs + crow(r, half)) ? s[r] : 0.0f;
             }
-        }
-
-        // ---- score_mod, mask_mod (partial blocks only), online softmax in base 2
-        const int dq_base = q_row - kv0;
-        float mx = -INFINITY;
-        if (partial) {
-#pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kvo = kvb * 32 + crow(r, half);
-                    float x = smod.apply(sacc[kvb][r], dq_base - kvo);
-                    x = mrow(kv0 + kvo) ? x : -INFINITY;
-                    sacc[kvb][r] = x;
-                    mx = fmaxf(mx, x);
-                }
         } else {
 #pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
+            for (int r = 0; r < 16; ++r) s[r] = smod.apply(s[r], dq_base - crow(r, half));
+            if (partial) {
+                asm volatile("" ::: "memory");
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kvo = kvb * 32 + crow(r, half);
-                    const float x = smod.apply(sacc[kvb][r], dq_base - kvo);
-                    sacc[kvb][r] = x;
-                    mx = fmaxf(mx, x);
-                }
-        }
-        mx = fmaxf(mx, swap_halves(mx));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-        const float alpha = fast_exp2(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.0f;
-        bf16x8 pf[2][2];
-#pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                u32x4 pk;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const float p0 = fast_exp2(sacc[kvb][8 * c + 2 * jj] - m_use);
-                    const float p1 = fast_exp2(sacc[kvb][8 * c + 2 * jj + 1] - m_use);
-                    psum += p0 + p1;
-                    pk[jj] = pack_bf16(p0, p1);
-                }
-                pf[kvb][c] = __builtin_bit_cast(bf16x8, pk);
+                for (int r = 0; r < 16; ++r) s[r] = mrow(kvs + crow(r, half)) ? s[r] : -INFINITY;
             }
-        l_run = l_run * alpha + psum;
-        if (__any(alpha != 1.0f)) {
+            float mx = s[0];
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db)
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+            mx = fmaxf(mx, swap_halves(mx));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
+            const float alpha = fast_exp2(m_run - m_use);
+            m_run = m_new;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r] - m_use);
+            l_run *= alpha;
+            if (__any(alpha != 1.0f)) {
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            }
         }
+        float psum = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            u32x4 pk;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                psum += s[8 * c + 2 * jj] + s[8 * c + 2 * jj + 1];
+                pk[jj] = pack_bf16(s[8 * c + 2 * jj], s[8 * c + 2 * jj + 1]);
+            }
+            pf[c] = __builtin_bit_cast(bf16x8, pk);
+        }
+        l_run += psum;
+    };
 
-        // ---- O^T += V^T P^T
+    // O^T += V^T P^T for the 32-key block kvb (compile-time) of the V tile in buffer BUF
+    auto pv = [&](auto buf_tag, int kvb, const bf16x8 (&pf)[2]) {
+        constexpr int BUF = decltype(buf_tag)::value;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const bf16x8 vf =
-                        *(const bf16x8*)(&Vt[buf][(db * 32 + l32) * VS + (kvb * 2 + c) * 16 + half * 8]);
-                    oacc[db] = mfma32(vf, pf[kvb][c], oacc[db]);
-                }
+            for (int c = 0; c < 2; ++c)
+                oacc[db] = mfma32(v_reader.read(smem_bytes + (2 + BUF) * (TILE * 2), kvb * 32 + 16 * c, db), pf[c], oacc[db]);
+    };
 
-        if (t + 1 < T) sstore(buf ^ 1);
+    // ---- prologue: K(0), V(0), K(1) in flight; S^T(0)
+    load_k(0);
+    load_v(0);
+    if (T > 1) load_k(1);
+    wait_vmem();
+    __syncthreads();
+    f32x16 s_cur[2], s_next[2];
+    qk(std::integral_constant<int, 0>{}, s_cur);
+
+    // One tile (t & 1 == BUF).  S^T of tile t+1 (MFMA) is issued next to the softmax of tile t (VALU),
+    // P V of the first 32 keys next to the softmax of the second 32.
+    auto tile_step = [&](int t, auto buf_tag, auto has_next_tag) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
+        // Everything this wave asked for has landed; after the barrier so has everyone else's, and
+        // nobody still reads K(t) [buffer BUF] or V(t-1) [buffer BUF ^ 1], which are refilled next.
+        wait_vmem();
         __syncthreads();
-        kv0 = kv0_next;
+        if (t + 2 < T) load_k(t + 2);
+        if constexpr (HAS_NEXT) load_v(t + 1);
+        const int kv0 = tile_kv0(t);
+        const bool partial = (t / a.sub) >= n_full;
+        bf16x8 pf[2];
+        if constexpr (HAS_NEXT) qk(std::integral_constant<int, BUF ^ 1>{}, s_next);
+        softmax(s_cur[0], kv0, partial, pf);
+        pv(buf_tag, 0, pf);
+        softmax(s_cur[1], kv0 + 32, partial, pf);
+        pv(buf_tag, 1, pf);
+        if constexpr (HAS_NEXT) {
+#pragma unroll
+            for (int kvb = 0; kvb < 2; ++kvb) s_cur[kvb] = s_next[kvb];
+        }
+    };
+    {
+        const std::integral_constant<int, 0> b0;
+        const std::integral_constant<int, 1> b1;
+        int t = 0;
+        for (; t + 2 < T; t += 2) {
+            tile_step(t, b0, std::true_type{});
+            tile_step(t + 1, b1, std::true_type{});
+        }
+        if (T - t == 2) {
+            tile_step(t, b0, std::true_type{});
+            tile_step(t + 1, b1, std::false_type{});
+        } else {
+            tile_step(t, b0, std::false_type{});
+        }
     }
 
     // ---- epilogue: O = O^T / l, LSE = ln 2 * (m + log2 l)
@@ -274,12 +258,12 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     if (half == 0) *lse_ptr = l_tot > 0.0f ? (m_run + fast_log2(l_tot)) * kLn2 : -INFINITY;
 }
 
-template <uint32_t MASK, uint32_t SCORE>
-int launch_fwd_variant(const FwdArgs& a, int D, int Bq, hipStream_t st) {
+template <uint32_t MASK, uint32_t SCORE, bool BOUNDED>
+int launch_fwd_shape(const FwdArgs& a, int D, int Bq, hipStream_t st) {
     const int units = a.B * a.Hkv;
     const unsigned grid = (unsigned)(((units + 7) / 8) * 8 * a.G * a.NR);
-#define FLEXATTN_LAUNCH(DD, NW)                                                                         \
-    hipLaunchKernelGGL((fwd_kernel<DD, NW, MASK, SCORE>), dim3(grid), dim3(NW * 64), 0, st, a);         \
+#define FLEXATTN_LAUNCH(DD, NW)                                                                            \
+    hipLaunchKernelGGL((fwd_kernel<DD, NW, MASK, SCORE, BOUNDED>), dim3(grid), dim3(NW * 64), 0, st, a);   \
     return FLEXATTN_OK;
     if (D == 128 && Bq == 128) { FLEXATTN_LAUNCH(128, 4) }
     if (D == 128 && Bq == 64) { FLEXATTN_LAUNCH(128, 2) }
@@ -287,6 +271,14 @@ int launch_fwd_variant(const FwdArgs& a, int D, int Bq, hipStream_t st) {
     if (D == 64 && Bq == 64) { FLEXATTN_LAUNCH(64, 2) }
 #undef FLEXATTN_LAUNCH
     return FLEXATTN_ERR_UNSUPPORTED;
+}
+
+template <uint32_t MASK, uint32_t SCORE>
+int launch_fwd_variant(const FwdArgs& a, int D, int Bq, hipStream_t st) {
+    if constexpr (SCORE & FLEXATTN_SCORE_SOFTCAP) {
+        if (2.0f * a.p.softcap * kLog2e <= 100.0f) return launch_fwd_shape<MASK, SCORE, true>(a, D, Bq, st);
+    }
+    return launch_fwd_shape<MASK, SCORE, false>(a, D, Bq, st);
 }
 
 }  // namespace flexattn

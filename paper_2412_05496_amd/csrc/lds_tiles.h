@@ -1,0 +1,122 @@
+// LDS tile helpers shared by the forward and backward kernels (gfx950).
+//
+// A tile is 64 rows x D bf16, row-major and UNPADDED in LDS, with the 16-byte chunks of every row
+// permuted by an XOR that depends on the row.  The permutation keeps both access patterns the
+// kernels use free of bank conflicts (64 banks x 4 bytes):
+//   row read         32 consecutive lanes read the same logical chunk of 32 consecutive rows
+//                    (A/B operand of an MFMA whose contraction runs along D);
+//   transposing read ds_read_b64_tr_b16: 16 lanes cover a 4-row x 16-column block and lane i gets
+//                    column i of the 4 rows (operand of an MFMA whose contraction runs along rows).
+// Tiles are filled straight from global memory (global_load_lds_dwordx4): each wave instruction
+// deposits 64 x 16 bytes contiguously in LDS, so the permutation is applied on the global side --
+// lane L fetches the chunk that belongs at LDS position L.
+//
+// Per-lane byte offsets for the reads are computed once (RowReader / TrReader) so that every
+// read in the main loops is "precomputed VGPR + immediate".
+#pragma once
+
+#include "flex_common.h"
+
+namespace flexattn {
+
+constexpr int kTileRows = 64;
+
+// XOR applied to the chunk index (0 .. D/8-1) of row `row`.
+template <int D>
+__device__ __forceinline__ constexpr int swz(int row) {
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+
+// Element offset of logical chunk `chunk` of row `row`.
+template <int D>
+__device__ __forceinline__ constexpr int tile_off(int row, int chunk) {
+    return row * D + 8 * (chunk ^ swz<D>(row));
+}
+
+// vmcnt(0): every global load (including loads into LDS) this wave issued has completed.
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+typedef __attribute__((address_space(3))) char lds_char;
+
+// Starts the copy of a 64 x D tile whose row 0 is at `g` (row stride `gs` elements) into `tile`.
+// All NW waves of the workgroup take part; completion needs wait_vmem() by every wave + a barrier.
+template <int D, int NW>
+struct TileLoader {
+    static constexpr int DC = D / 8;            // chunks per row
+    static constexpr int RPI = 64 / DC;         // rows per wave instruction (1 KiB)
+    static constexpr int NI = DC / NW;          // instructions per wave
+    static_assert(DC % NW == 0, "tile must split evenly over the waves");
+    int32_t off[NI];                            // per-lane element offset from the tile's first row
+    int wave;
+    __device__ __forceinline__ TileLoader(int64_t gs, int wave_, int lane) : wave(wave_) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int I = i * NW + wave;
+            const int row = I * RPI + lane / DC;
+            off[i] = (int32_t)(row * gs) + (((lane % DC) ^ swz<D>(row)) * 8);
+        }
+    }
+    __device__ __forceinline__ void start(bf16* tile, const bf16* g) const {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int I = i * NW + wave;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + off[i]),
+                                             (__attribute__((address_space(3))) void*)(tile + I * 512), 16, 0, 0);
+        }
+    }
+};
+
+// Row reads: fragment (row0 + lane % 32, dims 16 ks + 8 half ..) for row0 a multiple of 32.
+template <int D>
+struct RowReader {
+    uint32_t off[D / 16];                       // byte offsets inside a tile, row0 = 0
+    __device__ __forceinline__ RowReader(int l32, int half) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) off[ks] = 2u * (uint32_t)tile_off<D>(l32, 2 * ks + half);
+    }
+    // `tile_bytes`: LDS byte address of the tile (wave-uniform); row0 and ks are compile-time
+    __device__ __forceinline__ bf16x8 read(uint32_t tile_bytes, int row0, int ks) const {
+        return *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(tile_bytes + off[ks] + 2u * row0 * D);
+    }
+};
+
+__device__ __forceinline__ u32x2 lds_read_tr4(uint32_t addr) {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)addr);
+    return __builtin_bit_cast(u32x2, v);
+}
+
+// Transposing reads: operand fragment of tile^T for one MFMA contracting over tile ROWS.  The
+// fragment's row (or column) index is tile column c0 + lane % 32; the eight k-slots of half
+// h = lane / 32 are tile rows r0 + 4 h + {0,1,2,3} and r0 + 8 + 4 h + {0,1,2,3} -- exactly the rows
+// that registers 0..7 of a 32x32 MFMA result starting at row r0 hold in a lane of that half.
+// r0 is a multiple of 16, c0 a multiple of 32.
+template <int D>
+struct TrReader {
+    uint32_t off[D / 32][2];                    // [column block][low / high four rows], r0 = 0
+    __device__ __forceinline__ TrReader(int lane) {
+        const int j = lane & 15, grp = lane >> 4;
+        const int row = 4 * (grp >> 1) + (j >> 2);
+#pragma unroll
+        for (int cb = 0; cb < D / 32; ++cb) {
+            const int col = cb * 32 + 16 * (grp & 1) + 4 * (j & 3);
+            off[cb][0] = 2u * (uint32_t)(tile_off<D>(row, col >> 3) + (col & 7));
+            off[cb][1] = 2u * (uint32_t)(tile_off<D>(row + 8, col >> 3) + (col & 7));
+        }
+    }
+    // r0 (multiple of 16) and cb are compile-time: swz depends on r0 only through (r0 >> 2) & 3 == 0
+    __device__ __forceinline__ bf16x8 read(uint32_t tile_bytes, int r0, int cb) const {
+        const u32x2 lo = lds_read_tr4(tile_bytes + off[cb][0] + 2u * r0 * D);
+        const u32x2 hi = lds_read_tr4(tile_bytes + off[cb][1] + 2u * r0 * D);
+        u32x4 f = {lo[0], lo[1], hi[0], hi[1]};
+        return __builtin_bit_cast(bf16x8, f);
+    }
+};
+
+// LDS byte address of a __shared__ object.
+template <typename T>
+__device__ __forceinline__ uint32_t lds_addr(const T* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) T*)p;
+}
+
+}  // namespace flexattn
