@@ -12,9 +12,13 @@
 //   bwd_dq_kernel      one workgroup per row of blocks of one (b, hq); walks the kv-blocks listed
 //                      for it; score tile transposed (S^T = K Q^T) so that dS^T is the B operand of
 //                      dQ^T += K^T dS^T and LSE / delta are per-lane scalars.
+// Tiles (Q, dO in the first kernel; K, V in the second) go from global memory straight into
+// XOR-swizzled LDS tiles, double buffered, one barrier per tile; the transposed operands
+// (dO^T, Q^T, K^T) come out of the same row-major tiles through transposing LDS reads.
 #pragma once
 
 #include "flex_common.h"
+#include "lds_tiles.h"
 
 namespace flexattn {
 
@@ -46,25 +50,6 @@ struct BwdArgs {
     float scale;
     flexattn_mod_params p;
 };
-
-// Position of element t (0..15) inside a 16-wide chunk of a transposed LDS tile; see fwd_kernel.h.
-__device__ __forceinline__ constexpr int tr_pos16(int t) { return 8 * ((t >> 2) & 1) + 4 * (t >> 3) + (t & 3); }
-
-// Writes a 4-row x 8-column unit (rows r..r+3 of a row-major tile, held as four 16-byte registers)
-// into a transposed tile T[col][row-position] with row stride TS elements.
-__device__ __forceinline__ void store_unit_transposed(bf16* T, int TS, int col0, int pos, const u32x4 (&u)[4]) {
-#pragma unroll
-    for (int wd = 0; wd < 4; ++wd) {
-        const uint32_t r0 = u[0][wd], r1 = u[1][wd], r2 = u[2][wd], r3 = u[3][wd];
-        u32x2 lo, hi;
-        lo[0] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);
-        lo[1] = __builtin_amdgcn_perm(r3, r2, 0x05040100u);
-        hi[0] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);
-        hi[1] = __builtin_amdgcn_perm(r3, r2, 0x07060302u);
-        *(u32x2*)(&T[(col0 + 2 * wd) * TS + pos]) = lo;
-        *(u32x2*)(&T[(col0 + 2 * wd + 1) * TS + pos]) = hi;
-    }
-}
 
 // ------------------------------------------------------------------------------------------
 template <int D>
@@ -99,22 +84,12 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const BwdArgs a) {
 // their accumulators through LDS at the end.
 template <int D, uint32_t MASK, uint32_t SCORE>
 __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
-    constexpr int DC = D / 8;
-    constexpr int NS = D + 8;           // natural tiles: [64 rows][D] padded
-    constexpr int TS = 64 + 8;          // transposed tiles: [D][64 rows] padded
-    constexpr int NU = 16 * DC;         // 4-row x 8-col units per 64 x D tile
-    constexpr int UPT = (NU + 255) / 256;
-    constexpr int TQ = 64;              // query rows per step
-
-    // one LDS block: natural Q and dO tiles, their transposes; reused for the final reduction
-    constexpr int kTileElems = 2 * TQ * NS + 2 * D * TS;
-    static_assert(sizeof(bf16) * kTileElems >= sizeof(float) * 4 * D * 32, "reduction buffer must fit");
-    __shared__ __attribute__((aligned(16))) bf16 smem[kTileElems];
-    __shared__ float s_lse[TQ], s_delta[TQ];
-    bf16* const Qn = smem;
-    bf16* const dOn = Qn + TQ * NS;
-    bf16* const Qt = dOn + TQ * NS;
-    bf16* const dOt = Qt + D * TS;
+    constexpr int TQ = 64;                         // query rows per step
+    constexpr int TILE = TQ * D;                   // elements per LDS tile
+    static_assert(sizeof(bf16) * 4 * TILE >= sizeof(float) * 4 * D * 32, "reduction buffer must fit");
+    // Q(even), Q(odd), dO(even), dO(odd); reused for the final reduction
+    __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];
+    __shared__ __attribute__((aligned(16))) float s_row[2][2][TQ];   // [buffer][lse2 | delta][row]
 
     // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
     const int units = a.B * a.Hkv;
@@ -153,8 +128,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
         }
 
     const int sub = a.Bq / TQ;          // query tiles per BlockMask row block
-    u32x4 qreg[UPT][4], doreg[UPT][4];
-    float lse_reg = 0.0f, delta_reg = 0.0f;
+    const TileLoader<D, 4> q_loader(a.q_ss, w, lane), do_loader(a.do_ss, w, lane);
+    const RowReader<D> row_reader(l32, half);
+    const TrReader<D> tr_reader(lane);
+    const uint32_t smem_bytes = lds_addr(smem);
 
     for (int g = 0; g < a.G; ++g) {
         const int hq = hkv * a.G + g;
@@ -175,58 +152,34 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
             return blk * a.Bq + s * TQ;
         };
-        auto gload = [&](int q0) {
-#pragma unroll
-            for (int i = 0; i < UPT; ++i) {
-                const int u = tid + i * 256;
-                if (NU % 256 == 0 || u < NU) {
-                    const int gq = u / DC, cc = u % DC;
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        qreg[i][r4] = *(const u32x4*)(q_base + (int64_t)(q0 + 4 * gq + r4) * a.q_ss + cc * 8);
-                        doreg[i][r4] = *(const u32x4*)(do_base + (int64_t)(q0 + 4 * gq + r4) * a.do_ss + cc * 8);
-                    }
-                }
-            }
-            if (tid < TQ) {
-                lse_reg = lse_base[q0 + tid];
-                delta_reg = delta_base[q0 + tid];
-            }
+        auto load_tiles = [&](int t, int q0) {
+            q_loader.start(smem + (t & 1) * TILE, q_base + (int64_t)q0 * a.q_ss);
+            do_loader.start(smem + (2 + (t & 1)) * TILE, do_base + (int64_t)q0 * a.do_ss);
         };
-        auto sstore = [&]() {
-#pragma unroll
-            for (int i = 0; i < UPT; ++i) {
-                const int u = tid + i * 256;
-                if (NU % 256 == 0 || u < NU) {
-                    const int gq = u / DC, cc = u % DC;
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        *(u32x4*)(&Qn[(4 * gq + r4) * NS + cc * 8]) = qreg[i][r4];
-                        *(u32x4*)(&dOn[(4 * gq + r4) * NS + cc * 8]) = doreg[i][r4];
-                    }
-                    const int pos = 16 * (gq >> 2) + tr_pos16(4 * (gq & 3));
-                    store_unit_transposed(Qt, TS, cc * 8, pos, qreg[i]);
-                    store_unit_transposed(dOt, TS, cc * 8, pos, doreg[i]);
-                }
-            }
-            if (tid < TQ) {
-                s_lse[tid] = lse_reg;
-                s_delta[tid] = delta_reg;
-            }
+        // per-row scalars of a tile: threads 0..63 fetch lse2, 64..127 delta
+        auto load_rows = [&](int q0) {
+            return tid < TQ ? lse_base[q0 + tid] : (tid < 2 * TQ ? delta_base[q0 + tid - TQ] : 0.0f);
+        };
+        auto store_rows = [&](int t, float v) {
+            if (tid < 2 * TQ) s_row[t & 1][tid / TQ][tid % TQ] = v;
         };
 
         int q0 = tile_q0(0);
-        gload(q0);
+        load_tiles(0, q0);
+        store_rows(0, load_rows(q0));
+        wait_vmem();
+        __syncthreads();
+
         for (int t = 0; t < T; ++t) {
-            __syncthreads();            // previous step's readers are done with the LDS tiles
-            sstore();
-            __syncthreads();
             const int q0_cur = q0;
+            float row_next = 0.0f;
             if (t + 1 < T) {
                 q0 = tile_q0(t + 1);
-                gload(q0);
+                load_tiles(t + 1, q0);       // buffer (t+1) & 1 was last read in step t-1
+                row_next = load_rows(q0);
             }
             const bool partial = (t / sub) >= n_full;
+            const uint32_t qt = smem_bytes + (t & 1) * (TILE * 2), dot = smem_bytes + (2 + (t & 1)) * (TILE * 2);
 
             // S = Q K^T and dP = dO V^T for this wave's 32 x 32 piece
             f32x16 sacc, dpacc;
@@ -236,39 +189,43 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
                 dpacc[r] = 0.0f;
             }
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                const bf16x8 qa = *(const bf16x8*)(&Qn[(32 * qh + l32) * NS + ks * 16 + half * 8]);
-                sacc = mfma32(qa, kf[ks], sacc);
+            for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(row_reader.read(qt, 32 * qh, ks), kf[ks], sacc);
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(row_reader.read(dot, 32 * qh, ks), vf[ks], dpacc);
+
+            // P = exp2(x - lse2), dS = P * (dP - delta) * g; row q = 32 qh + crow(r, half)
+            f32x4 lse4[4], del4[4];
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                lse4[rg] = *(const f32x4*)(&s_row[t & 1][0][32 * qh + 8 * rg + 4 * half]);
+                del4[rg] = *(const f32x4*)(&s_row[t & 1][1][32 * qh + 8 * rg + 4 * half]);
             }
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                const bf16x8 da = *(const bf16x8*)(&dOn[(32 * qh + l32) * NS + ks * 16 + half * 8]);
-                dpacc = mfma32(da, vf[ks], dpacc);
+            for (int r = 0; r < 16; ++r) {
+                const int qi = q0_cur + 32 * qh + crow(r, half);
+                float gr;
+                const float x = smod.apply_with_grad(sacc[r], qi - kv_lane, gr);
+                const float pe = fast_exp2(x - lse4[r >> 2][r & 3]);
+                sacc[r] = pe;
+                dpacc[r] = pe * (dpacc[r] - del4[r >> 2][r & 3]) * gr;
             }
-
-            // P = exp2(x - lse2), dS = P * (dP - delta) * dscore; row q = 32 qh + crow(r, half)
+            if (partial) {
+                asm volatile("" ::: "memory");   // keep this a branch
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const MaskRow<MASK> mrow(a.p, b, hq, q0_cur + 32 * qh + crow(r, half));
+                    const bool keep = mrow(kv_lane);
+                    sacc[r] = keep ? sacc[r] : 0.0f;
+                    dpacc[r] = keep ? dpacc[r] : 0.0f;
+                }
+            }
             u32x4 pk[2], dsk[2];
 #pragma unroll
             for (int c = 0; c < 2; ++c)
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) {
-                    float pv[2], dsv[2];
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const int r = 8 * c + 2 * jj + e;
-                        const int ql = 32 * qh + crow(r, half);
-                        const int qi = q0_cur + ql;
-                        const float x = smod.apply(sacc[r], qi - kv_lane);
-                        float pe = fast_exp2(x - s_lse[ql]);
-                        if (partial) {
-                            const MaskRow<MASK> mrow(a.p, b, hq, qi);
-                            pe = mrow(kv_lane) ? pe : 0.0f;
-                        }
-                        pv[e] = pe;
-                        dsv[e] = pe * (dpacc[r] - s_delta[ql]) * smod.dscore(x);
-                    }
-                    pk[c][jj] = pack_bf16(pv[0], pv[1]);
-                    dsk[c][jj] = pack_bf16(dsv[0], dsv[1]);
+                    pk[c][jj] = pack_bf16(sacc[8 * c + 2 * jj], sacc[8 * c + 2 * jj + 1]);
+                    dsk[c][jj] = pack_bf16(dpacc[8 * c + 2 * jj], dpacc[8 * c + 2 * jj + 1]);
                 }
 
             // dV^T += dO^T P, dK^T += Q^T dS  (contraction over this wave's 32 query rows)
@@ -276,19 +233,18 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
-                    const int off = (db * 32 + l32) * TS + (2 * qh + c) * 16 + half * 8;
-                    const bf16x8 dot = *(const bf16x8*)(&dOt[off]);
-                    const bf16x8 qt = *(const bf16x8*)(&Qt[off]);
-                    dv[db] = mfma32(dot, __builtin_bit_cast(bf16x8, pk[c]), dv[db]);
-                    dk[db] = mfma32(qt, __builtin_bit_cast(bf16x8, dsk[c]), dk[db]);
+                    dv[db] = mfma32(tr_reader.read(dot, 32 * qh + 16 * c, db), __builtin_bit_cast(bf16x8, pk[c]), dv[db]);
+                    dk[db] = mfma32(tr_reader.read(qt, 32 * qh + 16 * c, db), __builtin_bit_cast(bf16x8, dsk[c]), dk[db]);
                 }
+
+            if (t + 1 < T) store_rows(t + 1, row_next);
+            wait_vmem();
+            __syncthreads();
         }
-        __syncthreads();                // before the next head overwrites the tiles
     }
 
     // ---- add the two query-halves through LDS and write dK, dV (bf16)
     float* red = (float*)smem;          // [key block][dK | dV][D][32 keys] floats
-    __syncthreads();
     if (qh == 1) {
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
@@ -300,6 +256,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
     }
     __syncthreads();
     if (qh == 0) {
+        const float kscale = a.scale * ScoreMod<SCORE>::grad_scale();
         bf16* dkp = a.dK + b * a.dk_sb + hkv * a.dk_sh + (int64_t)kv_lane * a.dk_ss;
         bf16* dvp = a.dV + b * a.dv_sb + hkv * a.dv_sh + (int64_t)kv_lane * a.dv_ss;
 #pragma unroll
@@ -310,7 +267,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int r = 4 * rg + e;
-                    k4[e] = (dk[db][r] + red[((kb * 2 + 0) * D + db * 32 + crow(r, half)) * 32 + l32]) * a.scale;
+                    k4[e] = (dk[db][r] + red[((kb * 2 + 0) * D + db * 32 + crow(r, half)) * 32 + l32]) * kscale;
                     v4[e] = dv[db][r] + red[((kb * 2 + 1) * D + db * 32 + crow(r, half)) * 32 + l32];
                 }
                 u32x2 ko, vo;
@@ -327,18 +284,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
 // ------------------------------------------------------------------------------------------
 // dQ.  NW waves, each owning 32 query rows of the row of blocks; structure of the forward kernel.
 template <int D, int NW, uint32_t MASK, uint32_t SCORE>
-__global__ __launch_bounds__(NW * 64, 1) void bwd_dq_kernel(const BwdArgs a) {
-    constexpr int NT = NW * 64;
+__global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     constexpr int Bq = NW * 32;
-    constexpr int DC = D / 8;
-    constexpr int NS = D + 8;
-    constexpr int TS = 64 + 8;
-    constexpr int NU = 16 * DC;
-    constexpr int UPT = (NU + NT - 1) / NT;
-
-    __shared__ __attribute__((aligned(16))) bf16 Kn[64 * NS];
-    __shared__ __attribute__((aligned(16))) bf16 Vn[64 * NS];
-    __shared__ __attribute__((aligned(16))) bf16 Kt[D * TS];
+    constexpr int TILE = 64 * D;
+    __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];   // K(even), K(odd), V(even), V(odd)
 
     const int units = a.B * a.Hkv;
     const int id = blockIdx.x, xcd = id & 7, kk = id >> 3;
@@ -383,42 +332,19 @@ __global__ __launch_bounds__(NW * 64, 1) void bwd_dq_kernel(const BwdArgs a) {
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
     const MaskRow<MASK> mrow(a.p, b, hq, q_row);
 
-    u32x4 kreg[UPT][4], vreg[UPT][4];
     auto tile_kv0 = [&](int t) {
         const int pos = t / sub, s = t - pos * sub;
         const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
         return blk * a.Bk + s * 64;
     };
-    auto gload = [&](int kv0) {
-#pragma unroll
-        for (int i = 0; i < UPT; ++i) {
-            const int u = tid + i * NT;
-            if (NU % NT == 0 || u < NU) {
-                const int gq = u / DC, cc = u % DC;
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    kreg[i][r4] = *(const u32x4*)(k_base + (int64_t)(kv0 + 4 * gq + r4) * a.k_ss + cc * 8);
-                    vreg[i][r4] = *(const u32x4*)(v_base + (int64_t)(kv0 + 4 * gq + r4) * a.v_ss + cc * 8);
-                }
-            }
-        }
+    const TileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
+    auto load_tiles = [&](int t, int kv0) {
+        k_loader.start(smem + (t & 1) * TILE, k_base + (int64_t)kv0 * a.k_ss);
+        v_loader.start(smem + (2 + (t & 1)) * TILE, v_base + (int64_t)kv0 * a.v_ss);
     };
-    auto sstore = [&]() {
-#pragma unroll
-        for (int i = 0; i < UPT; ++i) {
-            const int u = tid + i * NT;
-            if (NU % NT == 0 || u < NU) {
-                const int gq = u / DC, cc = u % DC;
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    *(u32x4*)(&Kn[(4 * gq + r4) * NS + cc * 8]) = kreg[i][r4];
-                    *(u32x4*)(&Vn[(4 * gq + r4) * NS + cc * 8]) = vreg[i][r4];
-                }
-                const int pos = 16 * (gq >> 2) + tr_pos16(4 * (gq & 3));
-                store_unit_transposed(Kt, TS, cc * 8, pos, kreg[i]);
-            }
-        }
-    };
+    const RowReader<D> row_reader(l32, half);
+    const TrReader<D> tr_reader(lane);
+    const uint32_t smem_bytes = lds_addr(smem);
 
     f32x16 dq[D / 32];
 #pragma unroll
@@ -427,21 +353,22 @@ __global__ __launch_bounds__(NW * 64, 1) void bwd_dq_kernel(const BwdArgs a) {
         for (int r = 0; r < 16; ++r) dq[db][r] = 0.0f;
 
     int kv0 = tile_kv0(0);
-    gload(kv0);
+    load_tiles(0, kv0);
+    wait_vmem();
+    __syncthreads();
+
     for (int t = 0; t < T; ++t) {
-        __syncthreads();
-        sstore();
-        __syncthreads();
         const int kv0_cur = kv0;
         if (t + 1 < T) {
             kv0 = tile_kv0(t + 1);
-            gload(kv0);
+            load_tiles(t + 1, kv0);          // buffer (t+1) & 1 was last read in step t-1
         }
         const bool partial = (t / sub) >= n_full;
+        const uint32_t kt = smem_bytes + (t & 1) * (TILE * 2), vt = smem_bytes + (2 + (t & 1)) * (TILE * 2);
 
-        u32x4 dsk[2][2];
 #pragma unroll
         for (int kvb = 0; kvb < 2; ++kvb) {
+            // S^T = K Q^T and dP^T = V dO^T for 32 keys
             f32x16 sacc, dpacc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -449,51 +376,45 @@ __global__ __launch_bounds__(NW * 64, 1) void bwd_dq_kernel(const BwdArgs a) {
                 dpacc[r] = 0.0f;
             }
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                const bf16x8 ka = *(const bf16x8*)(&Kn[(kvb * 32 + l32) * NS + ks * 16 + half * 8]);
-                sacc = mfma32(ka, qf[ks], sacc);
+            for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(row_reader.read(kt, kvb * 32, ks), qf[ks], sacc);
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(row_reader.read(vt, kvb * 32, ks), dof[ks], dpacc);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kv = kv0_cur + kvb * 32 + crow(r, half);
+                float gr;
+                const float x = smod.apply_with_grad(sacc[r], q_row - kv, gr);
+                const float pe = fast_exp2(x - lse2);
+                dpacc[r] = pe * (dpacc[r] - delta) * gr;
             }
+            if (partial) {
+                asm volatile("" ::: "memory");   // keep this a branch
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                const bf16x8 va = *(const bf16x8*)(&Vn[(kvb * 32 + l32) * NS + ks * 16 + half * 8]);
-                dpacc = mfma32(va, dof[ks], dpacc);
+                for (int r = 0; r < 16; ++r) dpacc[r] = mrow(kv0_cur + kvb * 32 + crow(r, half)) ? dpacc[r] : 0.0f;
             }
+            // dQ^T += K^T dS^T
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+            for (int c = 0; c < 2; ++c) {
+                u32x4 dsk;
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    float dsv[2];
+                for (int jj = 0; jj < 4; ++jj) dsk[jj] = pack_bf16(dpacc[8 * c + 2 * jj], dpacc[8 * c + 2 * jj + 1]);
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const int r = 8 * c + 2 * jj + e;
-                        const int kv = kv0_cur + kvb * 32 + crow(r, half);
-                        const float x = smod.apply(sacc[r], q_row - kv);
-                        float pe = fast_exp2(x - lse2);
-                        if (partial) pe = mrow(kv) ? pe : 0.0f;
-                        dsv[e] = pe * (dpacc[r] - delta) * smod.dscore(x);
-                    }
-                    dsk[kvb][c][jj] = pack_bf16(dsv[0], dsv[1]);
-                }
+                for (int db = 0; db < D / 32; ++db)
+                    dq[db] = mfma32(tr_reader.read(kt, kvb * 32 + 16 * c, db), __builtin_bit_cast(bf16x8, dsk), dq[db]);
+            }
         }
-        // dQ^T += K^T dS^T
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const bf16x8 kt = *(const bf16x8*)(&Kt[(db * 32 + l32) * TS + (kvb * 2 + c) * 16 + half * 8]);
-                    dq[db] = mfma32(kt, __builtin_bit_cast(bf16x8, dsk[kvb][c]), dq[db]);
-                }
+        wait_vmem();
+        __syncthreads();
     }
 
+    const float qscale = a.scale * ScoreMod<SCORE>::grad_scale();
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
             u32x2 pk;
-            pk[0] = pack_bf16(dq[db][4 * rg] * a.scale, dq[db][4 * rg + 1] * a.scale);
-            pk[1] = pack_bf16(dq[db][4 * rg + 2] * a.scale, dq[db][4 * rg + 3] * a.scale);
+            pk[0] = pack_bf16(dq[db][4 * rg] * qscale, dq[db][4 * rg + 1] * qscale);
+            pk[1] = pack_bf16(dq[db][4 * rg + 2] * qscale, dq[db][4 * rg + 3] * qscale);
             *(u32x2*)(dq_ptr + db * 32 + 8 * rg + 4 * half) = pk;
         }
 }

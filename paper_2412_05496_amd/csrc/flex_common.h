@@ -159,6 +159,21 @@ struct ScoreMod {
             return 1.0f;
         }
     }
+
+    // apply() plus the derivative d score_mod / d s up to the constant factor grad_scale():
+    // for the soft-cap, 1 - tanh^2 = 4 r (1 - r) with r from cap_r(), so g = r - r^2 and the 4 is
+    // folded into the final scaling of dQ / dK.
+    __device__ __forceinline__ float apply_with_grad(float acc, int dq, float& g) const {
+        if constexpr (kCap) {
+            const float r = cap_r(acc, dq);
+            g = __builtin_fmaf(-r, r, r);
+            return __builtin_fmaf(-2.0f * capl2, r, capl2);
+        } else {
+            g = 1.0f;
+            return pre(acc, dq);
+        }
+    }
+    static constexpr float grad_scale() { return kCap ? 4.0f : 1.0f; }
 };
 
 // ---------------------------------------------------------------------------------------
