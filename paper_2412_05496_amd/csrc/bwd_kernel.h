@@ -17,6 +17,8 @@
 // (dO^T, Q^T, K^T) come out of the same row-major tiles through transposing LDS reads.
 #pragma once
 
+#include <type_traits>
+
 #include "flex_common.h"
 #include "lds_tiles.h"
 
@@ -79,17 +81,19 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const BwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// dK, dV.  256 threads = 4 waves; wave w owns keys 32 * (w & 1) .. +32 of the 64-key tile and
-// query rows 32 * (w >> 1) .. +32 of every 64-row query tile; the two waves that share keys add
-// their accumulators through LDS at the end.
+// dK, dV.  256 threads = 4 waves; one workgroup per 64 keys.  The listed q-blocks are walked in
+// steps of two 64-row half-tiles; wave w owns keys 32 * (w & 1) .. +32 and the half-tile w >> 1,
+// which it processes as two 32 x 32 score blocks so that the MFMAs of one block sit next to the
+// exp / dS arithmetic of the other.  The two waves that share keys add their accumulators
+// through LDS at the end.
 template <int D, uint32_t MASK, uint32_t SCORE>
 __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
-    constexpr int TQ = 64;                         // query rows per step
-    constexpr int TILE = TQ * D;                   // elements per LDS tile
-    static_assert(sizeof(bf16) * 4 * TILE >= sizeof(float) * 4 * D * 32, "reduction buffer must fit");
-    // Q(even), Q(odd), dO(even), dO(odd); reused for the final reduction
-    __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];
-    __shared__ __attribute__((aligned(16))) float s_row[2][2][TQ];   // [buffer][lse2 | delta][row]
+    constexpr int HQ = 64;                         // query rows per half-tile
+    constexpr int TILE = HQ * D;                   // elements per LDS tile
+    // per buffer: Q half a, Q half b, dO half a, dO half b; two buffers; reused for the final reduction
+    __shared__ __attribute__((aligned(1024))) bf16 smem[8 * TILE];
+    __shared__ __attribute__((aligned(16))) float s_row[2][2][2 * HQ];   // [buffer][lse2 | delta][row]
+    static_assert(sizeof(bf16) * 8 * TILE >= sizeof(float) * 4 * D * 32, "reduction buffer must fit");
 
     // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
     const int units = a.B * a.Hkv;
@@ -127,11 +131,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             dv[db][r] = 0.0f;
         }
 
-    const int sub = a.Bq / TQ;          // query tiles per BlockMask row block
+    const int sub = a.Bq / HQ;          // half-tiles per BlockMask row block
     const TileLoader<D, 4> q_loader(a.q_ss, w, lane), do_loader(a.do_ss, w, lane);
-    const RowReader<D> row_reader(l32, half);
-    const TrReader<D> tr_reader(lane);
-    const uint32_t smem_bytes = lds_addr(smem);
+    // per-lane LDS addresses of this wave's half-tile (Q copy; the dO copy is 2 tiles further on)
+    const uint32_t my_tile = lds_addr(smem) + qh * (TILE * 2);
+    const RowReader<D> row_reader(l32, half, my_tile);
+    const TrReader<D> tr_reader(lane, my_tile);
 
     for (int g = 0; g < a.G; ++g) {
         const int hq = hkv * a.G + g;
@@ -139,108 +144,128 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
         const int n_full = a.full_q_num[line], n_part = a.q_num[line];
         const int32_t* full_idx = a.full_q_idx + line * a.NR;
         const int32_t* part_idx = a.q_idx + line * a.NR;
-        const int T = (n_full + n_part) * sub;
-        if (T == 0) continue;
+        const int H = (n_full + n_part) * sub;      // half-tiles to visit
+        if (H == 0) continue;
+        const int U = (H + 1) / 2;                  // steps
         const bf16* q_base = a.Q + b * a.q_sb + hq * a.q_sh;
         const bf16* do_base = a.dO + b * a.do_sb + hq * a.do_sh;
         const float* lse_base = a.lse2 + ((int64_t)b * a.Hq + hq) * a.q_len;
         const float* delta_base = a.delta + ((int64_t)b * a.Hq + hq) * a.q_len;
         const ScoreMod<SCORE> smod(a.p, hq, a.scale);
 
-        auto tile_q0 = [&](int t) {
-            const int pos = t / sub, s = t - pos * sub;
+        auto half_q0 = [&](int h) {                 // first query row of half-tile h (h < H)
+            const int pos = h / sub, s = h - pos * sub;
             const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
-            return blk * a.Bq + s * TQ;
+            return blk * a.Bq + s * HQ;
         };
-        auto load_tiles = [&](int t, int q0) {
-            q_loader.start(smem + (t & 1) * TILE, q_base + (int64_t)q0 * a.q_ss);
-            do_loader.start(smem + (2 + (t & 1)) * TILE, do_base + (int64_t)q0 * a.do_ss);
+        // starts the loads of step u into buffer u & 1; returns this thread's row scalar
+        auto load_step = [&](int u) {
+            bf16* buf = smem + (u & 1) * 4 * TILE;
+            const int qa = half_q0(2 * u);
+            const bool has_b = 2 * u + 1 < H;
+            const int qb = has_b ? half_q0(2 * u + 1) : qa;
+            // row scalars first: waiting for them later must not wait for the tiles behind them
+            const int rr = tid & (2 * HQ - 1);
+            const int qrow = (rr < HQ ? qa : qb) + (rr & (HQ - 1));
+            const float v = tid < 2 * HQ ? lse_base[qrow] : delta_base[qrow];
+            q_loader.start(buf, q_base + (int64_t)qa * a.q_ss);
+            do_loader.start(buf + 2 * TILE, do_base + (int64_t)qa * a.do_ss);
+            if (has_b) {
+                q_loader.start(buf + TILE, q_base + (int64_t)qb * a.q_ss);
+                do_loader.start(buf + 3 * TILE, do_base + (int64_t)qb * a.do_ss);
+            }
+            return v;
         };
-        // per-row scalars of a tile: threads 0..63 fetch lse2, 64..127 delta
-        auto load_rows = [&](int q0) {
-            return tid < TQ ? lse_base[q0 + tid] : (tid < 2 * TQ ? delta_base[q0 + tid - TQ] : 0.0f);
-        };
-        auto store_rows = [&](int t, float v) {
-            if (tid < 2 * TQ) s_row[t & 1][tid / TQ][tid % TQ] = v;
+        // lse2 is stored as the row constant of ScoreMod::p_with_grad
+        auto store_rows = [&](int u, float v) {
+            s_row[u & 1][tid >> 7][tid & (2 * HQ - 1)] = tid < 2 * HQ ? smod.row_const(v) : v;
         };
 
-        int q0 = tile_q0(0);
-        load_tiles(0, q0);
-        store_rows(0, load_rows(q0));
+        store_rows(0, load_step(0));
         wait_vmem();
         __syncthreads();
 
-        for (int t = 0; t < T; ++t) {
-            const int q0_cur = q0;
+        // One step on buffer BUF (compile-time, so that every LDS read is "VGPR + immediate").
+        auto step = [&](int u, auto buf_tag) {
+            constexpr int BUF = decltype(buf_tag)::value;
             float row_next = 0.0f;
-            if (t + 1 < T) {
-                q0 = tile_q0(t + 1);
-                load_tiles(t + 1, q0);       // buffer (t+1) & 1 was last read in step t-1
-                row_next = load_rows(q0);
-            }
-            const bool partial = (t / sub) >= n_full;
-            const uint32_t qt = smem_bytes + (t & 1) * (TILE * 2), dot = smem_bytes + (2 + (t & 1)) * (TILE * 2);
+            if (u + 1 < U) row_next = load_step(u + 1);     // buffer BUF ^ 1 was last read in step u-1
+            const int h_mine = 2 * u + qh;
+            if (h_mine < H) {
+                const int q0 = half_q0(h_mine);
+                const bool partial = (h_mine / sub) >= n_full;
+                constexpr uint32_t qt = BUF * 4 * (TILE * 2), dot = (BUF * 4 + 2) * (TILE * 2);
+                const float* lrow = &s_row[BUF][0][HQ * qh];
+                const float* drow = &s_row[BUF][1][HQ * qh];
 
-            // S = Q K^T and dP = dO V^T for this wave's 32 x 32 piece
-            f32x16 sacc, dpacc;
+                // S = Q K^T and dP = dO V^T for both 32-row blocks of this wave
+                f32x16 sacc[2], dpacc[2];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                sacc[r] = 0.0f;
-                dpacc[r] = 0.0f;
-            }
+                for (int j = 0; j < 2; ++j) {
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(row_reader.read(qt, 32 * qh, ks), kf[ks], sacc);
+                    for (int r = 0; r < 16; ++r) {
+                        sacc[j][r] = 0.0f;
+                        dpacc[j][r] = 0.0f;
+                    }
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(row_reader.read(dot, 32 * qh, ks), vf[ks], dpacc);
-
-            // P = exp2(x - lse2), dS = P * (dP - delta) * g; row q = 32 qh + crow(r, half)
-            f32x4 lse4[4], del4[4];
+                    for (int ks = 0; ks < D / 16; ++ks) sacc[j] = mfma32(row_reader.read(qt, 32 * j, ks), kf[ks], sacc[j]);
 #pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                lse4[rg] = *(const f32x4*)(&s_row[t & 1][0][32 * qh + 8 * rg + 4 * half]);
-                del4[rg] = *(const f32x4*)(&s_row[t & 1][1][32 * qh + 8 * rg + 4 * half]);
-            }
+                    for (int ks = 0; ks < D / 16; ++ks) dpacc[j] = mfma32(row_reader.read(dot, 32 * j, ks), vf[ks], dpacc[j]);
+                }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int qi = q0_cur + 32 * qh + crow(r, half);
-                float gr;
-                const float x = smod.apply_with_grad(sacc[r], qi - kv_lane, gr);
-                const float pe = fast_exp2(x - lse4[r >> 2][r & 3]);
-                sacc[r] = pe;
-                dpacc[r] = pe * (dpacc[r] - del4[r >> 2][r & 3]) * gr;
-            }
-            if (partial) {
-                asm volatile("" ::: "memory");   // keep this a branch
+                for (int j = 0; j < 2; ++j) {
+                    // P = exp2(x - lse2), dS = P * (dP - delta) * g; row = 32 j + crow(r, half)
+                    f32x4 rc4[4], del4[4];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const MaskRow<MASK> mrow(a.p, b, hq, q0_cur + 32 * qh + crow(r, half));
-                    const bool keep = mrow(kv_lane);
-                    sacc[r] = keep ? sacc[r] : 0.0f;
-                    dpacc[r] = keep ? dpacc[r] : 0.0f;
+                    for (int rg = 0; rg < 4; ++rg) {
+                        rc4[rg] = *(const f32x4*)(lrow + 32 * j + 8 * rg + 4 * half);
+                        del4[rg] = *(const f32x4*)(drow + 32 * j + 8 * rg + 4 * half);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int qi = q0 + 32 * j + crow(r, half);
+                        float gr;
+                        const float pe = smod.p_with_grad(sacc[j][r], qi - kv_lane, rc4[r >> 2][r & 3], gr);
+                        sacc[j][r] = pe;
+                        dpacc[j][r] = pe * (dpacc[j][r] - del4[r >> 2][r & 3]) * gr;
+                    }
+                    if (partial) {
+                        asm volatile("" ::: "memory");   // keep this a branch
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const MaskRow<MASK> mrow(a.p, b, hq, q0 + 32 * j + crow(r, half));
+                            const bool keep = mrow(kv_lane);
+                            sacc[j][r] = keep ? sacc[j][r] : 0.0f;
+                            dpacc[j][r] = keep ? dpacc[j][r] : 0.0f;
+                        }
+                    }
+                    // dV^T += dO^T P, dK^T += Q^T dS  (contraction over these 32 query rows)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        u32x4 pk, dsk;
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) {
+                            pk[jj] = pack_bf16(sacc[j][8 * c + 2 * jj], sacc[j][8 * c + 2 * jj + 1]);
+                            dsk[jj] = pack_bf16(dpacc[j][8 * c + 2 * jj], dpacc[j][8 * c + 2 * jj + 1]);
+                        }
+#pragma unroll
+                        for (int db = 0; db < D / 32; ++db) {
+                            dv[db] = mfma32(tr_reader.read(dot, 32 * j + 16 * c, db), __builtin_bit_cast(bf16x8, pk), dv[db]);
+                            dk[db] = mfma32(tr_reader.read(qt, 32 * j + 16 * c, db), __builtin_bit_cast(bf16x8, dsk), dk[db]);
+                        }
+                    }
                 }
             }
-            u32x4 pk[2], dsk[2];
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    pk[c][jj] = pack_bf16(sacc[8 * c + 2 * jj], sacc[8 * c + 2 * jj + 1]);
-                    dsk[c][jj] = pack_bf16(dpacc[8 * c + 2 * jj], dpacc[8 * c + 2 * jj + 1]);
-                }
-
-            // dV^T += dO^T P, dK^T += Q^T dS  (contraction over this wave's 32 query rows)
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    dv[db] = mfma32(tr_reader.read(dot, 32 * qh + 16 * c, db), __builtin_bit_cast(bf16x8, pk[c]), dv[db]);
-                    dk[db] = mfma32(tr_reader.read(qt, 32 * qh + 16 * c, db), __builtin_bit_cast(bf16x8, dsk[c]), dk[db]);
-                }
-
-            if (t + 1 < T) store_rows(t + 1, row_next);
+            if (u + 1 < U) store_rows(u + 1, row_next);
             wait_vmem();
             __syncthreads();
+        };
+        int u = 0;
+        for (; u + 1 < U; u += 2) {
+            step(u, std::integral_constant<int, 0>{});
+            step(u + 1, std::integral_constant<int, 1>{});
         }
+        if (u < U) step(u, std::integral_constant<int, 0>{});
     }
 
     // ---- add the two query-halves through LDS and write dK, dV (bf16)
@@ -342,9 +367,9 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
         k_loader.start(smem + (t & 1) * TILE, k_base + (int64_t)kv0 * a.k_ss);
         v_loader.start(smem + (2 + (t & 1)) * TILE, v_base + (int64_t)kv0 * a.v_ss);
     };
-    const RowReader<D> row_reader(l32, half);
-    const TrReader<D> tr_reader(lane);
-    const uint32_t smem_bytes = lds_addr(smem);
+    const RowReader<D> row_reader(l32, half, lds_addr(smem));
+    const TrReader<D> tr_reader(lane, lds_addr(smem));
+    const float rc = smod.row_const(lse2);
 
     f32x16 dq[D / 32];
 #pragma unroll
@@ -357,14 +382,16 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     wait_vmem();
     __syncthreads();
 
-    for (int t = 0; t < T; ++t) {
+    // One tile on buffer BUF (compile-time, so that every LDS read is "VGPR + immediate").
+    auto step = [&](int t, auto buf_tag) {
+        constexpr int BUF = decltype(buf_tag)::value;
         const int kv0_cur = kv0;
         if (t + 1 < T) {
             kv0 = tile_kv0(t + 1);
-            load_tiles(t + 1, kv0);          // buffer (t+1) & 1 was last read in step t-1
+            load_tiles(t + 1, kv0);          // buffer BUF ^ 1 was last read in step t-1
         }
         const bool partial = (t / sub) >= n_full;
-        const uint32_t kt = smem_bytes + (t & 1) * (TILE * 2), vt = smem_bytes + (2 + (t & 1)) * (TILE * 2);
+        constexpr uint32_t kt = BUF * (TILE * 2), vt = (2 + BUF) * (TILE * 2);
 
 #pragma unroll
         for (int kvb = 0; kvb < 2; ++kvb) {
@@ -383,8 +410,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
             for (int r = 0; r < 16; ++r) {
                 const int kv = kv0_cur + kvb * 32 + crow(r, half);
                 float gr;
-                const float x = smod.apply_with_grad(sacc[r], q_row - kv, gr);
-                const float pe = fast_exp2(x - lse2);
+                const float pe = smod.p_with_grad(sacc[r], q_row - kv, rc, gr);
                 dpacc[r] = pe * (dpacc[r] - delta) * gr;
             }
             if (partial) {
@@ -405,6 +431,14 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
         }
         wait_vmem();
         __syncthreads();
+    };
+    {
+        int t = 0;
+        for (; t + 1 < T; t += 2) {
+            step(t, std::integral_constant<int, 0>{});
+            step(t + 1, std::integral_constant<int, 1>{});
+        }
+        if (t < T) step(t, std::integral_constant<int, 0>{});
     }
 
     const float qscale = a.scale * ScoreMod<SCORE>::grad_scale();

@@ -174,6 +174,20 @@ struct ScoreMod {
         }
     }
     static constexpr float grad_scale() { return kCap ? 4.0f : 1.0f; }
+
+    // Backward: P = exp(score' - LSE) from the raw dot product, with the row's constant folded in.
+    // row_const() maps LSE * log2(e) (+inf for a row without visible keys) to that constant.
+    __device__ __forceinline__ float row_const(float lse2) const { return kCap ? capl2 - lse2 : -lse2; }
+    __device__ __forceinline__ float p_with_grad(float acc, int dq, float rc, float& g) const {
+        if constexpr (kCap) {
+            const float r = cap_r(acc, dq);
+            g = __builtin_fmaf(-r, r, r);
+            return fast_exp2(__builtin_fmaf(-2.0f * capl2, r, rc));
+        } else {
+            g = 1.0f;
+            return fast_exp2(pre(acc, dq) + rc);
+        }
+    }
 };
 
 // ---------------------------------------------------------------------------------------

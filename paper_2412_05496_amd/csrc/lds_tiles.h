@@ -70,9 +70,11 @@ struct TileLoader {
 template <int D>
 struct RowReader {
     uint32_t off[D / 16];                       // byte offsets inside a tile, row0 = 0
-    __device__ __forceinline__ RowReader(int l32, int half) {
+    // `base`: a per-lane byte offset added to every read (e.g. the LDS address of the buffer set
+    // plus a wave-specific tile), so that reads are "this VGPR + immediate"
+    __device__ __forceinline__ RowReader(int l32, int half, uint32_t base = 0) {
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) off[ks] = 2u * (uint32_t)tile_off<D>(l32, 2 * ks + half);
+        for (int ks = 0; ks < D / 16; ++ks) off[ks] = base + 2u * (uint32_t)tile_off<D>(l32, 2 * ks + half);
     }
     // `tile_bytes`: LDS byte address of the tile (wave-uniform); row0 and ks are compile-time
     __device__ __forceinline__ bf16x8 read(uint32_t tile_bytes, int row0, int ks) const {
@@ -94,14 +96,14 @@ __device__ __forceinline__ u32x2 lds_read_tr4(uint32_t addr) {
 template <int D>
 struct TrReader {
     uint32_t off[D / 32][2];                    // [column block][low / high four rows], r0 = 0
-    __device__ __forceinline__ TrReader(int lane) {
+    __device__ __forceinline__ TrReader(int lane, uint32_t base = 0) {
         const int j = lane & 15, grp = lane >> 4;
         const int row = 4 * (grp >> 1) + (j >> 2);
 #pragma unroll
         for (int cb = 0; cb < D / 32; ++cb) {
             const int col = cb * 32 + 16 * (grp & 1) + 4 * (j & 3);
-            off[cb][0] = 2u * (uint32_t)(tile_off<D>(row, col >> 3) + (col & 7));
-            off[cb][1] = 2u * (uint32_t)(tile_off<D>(row + 8, col >> 3) + (col & 7));
+            off[cb][0] = base + 2u * (uint32_t)(tile_off<D>(row, col >> 3) + (col & 7));
+            off[cb][1] = base + 2u * (uint32_t)(tile_off<D>(row + 8, col >> 3) + (col & 7));
         }
     }
     // r0 (multiple of 16) and cb are compile-time: swz depends on r0 only through (r0 >> 2) & 3 == 0
