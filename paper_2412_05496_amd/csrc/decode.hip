@@ -2,19 +2,21 @@
 // into the KV-block walk as in section 5.1) and the partial-softmax combine.
 //
 // The path is bound by reading K and V once from HBM.  One WAVE owns one (sequence, KV head,
-// KV split): it walks its logical pages, looks each up in the page table and reads K rows straight
-// from the pool into the A-operand layout of S^T = K Q^T (each lane: 16-byte pieces of one key
-// row), with the G query heads of the group as (zero-padded) columns, so K and V are read once
-// per KV head, never once per query head.  V rows are read 16 bytes per lane, four keys at a
-// time, transposed through a wave-private LDS tile and used as V^T in O^T += V^T P^T.  No
-// workgroup barrier is needed.  Each wave leaves (m, l, O) of its split in the workspace; the
-// combine kernel merges the splits of a (sequence, head) with the usual log-sum-exp weights.
+// KV split) and never synchronises with another: it walks its logical pages 32 keys at a time,
+// looks each key's page up in the page table and pulls the K and V rows straight from the pool into
+// its private, XOR-swizzled LDS tiles (global_load_lds_dwordx4: every wave instruction moves 1 KiB
+// of whole 256-byte rows, so the page gather is fully coalesced).  S^T = K Q^T takes K rows from
+// LDS as the A operand with the G query heads of the group as (zero-padded) columns of the B
+// operand, so K and V are read once per KV head, never once per query head; V^T comes out of the
+// row-major V tile through the transposing LDS read.  Each wave leaves (m, l, O) of its split in
+// the workspace; the combine kernel merges the splits of a (sequence, head) with log-sum-exp weights.
 #include "flex_common.h"
+#include "lds_tiles.h"
 
 namespace flexattn {
 
 constexpr int kDecWaves = 4;       // waves (= splits) per workgroup
-constexpr int kDecTile = 64;       // keys per inner tile
+constexpr int kDecTile = 32;       // keys per inner tile
 constexpr int kDecSplit = 512;     // keys per split
 
 struct DecodeArgs {
@@ -34,15 +36,13 @@ struct DecodeArgs {
     float* LSE;
 };
 
-__device__ __forceinline__ constexpr int dec_vt_pos16(int t) { return 8 * ((t >> 2) & 1) + 4 * (t >> 3) + (t & 3); }
-
 template <int D, uint32_t SCORE>
 __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const DecodeArgs a) {
-    constexpr int DC = D / 8;
-    constexpr int VS = kDecTile + 8;
-    constexpr int NVU = (kDecTile / 4) * DC;   // 4-key x 8-dim units per tile
-    constexpr int NVT = NVU / 64;              // per lane
-    __shared__ __attribute__((aligned(16))) bf16 Vt_all[kDecWaves][D * VS];
+    constexpr int DC = D / 8;                  // 16-byte chunks per row
+    constexpr int RPI = 64 / DC;               // rows per wave instruction
+    constexpr int NI = kDecTile / RPI;         // instructions per tile and tensor
+    constexpr int TILE = kDecTile * D;         // elements
+    __shared__ __attribute__((aligned(1024))) bf16 smem[kDecWaves * 2 * TILE];   // per wave: K tile, V tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int b = blockIdx.x / a.Hkv, hkv = blockIdx.x % a.Hkv;
@@ -51,7 +51,8 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
     const int tok_begin = split * kDecSplit;
     if (tok_begin >= ctx) return;                       // wave-uniform; the kernel has no barriers
     const int tok_end = min(ctx, tok_begin + kDecSplit);
-    bf16* Vt = Vt_all[wave];
+    bf16* k_tile = smem + wave * 2 * TILE;
+    bf16* v_tile = k_tile + TILE;
 
     const int g_lane = l32;                             // query head of the group held by this lane
     const bool g_ok = g_lane < a.G;
@@ -71,6 +72,8 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
     const int32_t* pt = a.page_table + (int64_t)b * a.pt_stride;
     const int page_mask = a.page_size - 1;
     const int64_t slab = (int64_t)a.page_size * D;      // elements per (page, head)
+    const RowReader<D> k_reader(l32, half, lds_addr(k_tile));
+    const TrReader<D> v_reader(lane, lds_addr(v_tile));
 
     f32x16 oacc[D / 32];
 #pragma unroll
@@ -80,106 +83,70 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
     float m_run = -INFINITY, l_run = 0.0f;
 
     for (int tok0 = tok_begin; tok0 < tok_end; tok0 += kDecTile) {
-        // ---- gather K rows (A operand of K Q^T) through the page table
-        bf16x8 kf[2][D / 16];
+        // ---- gather 32 K rows and 32 V rows through the page table, straight into LDS
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb) {
-            const int tok = min(tok0 + kvb * 32 + l32, ctx - 1);     // rows past the context re-read the last key
+        for (int i = 0; i < NI; ++i) {
+            const int row = i * RPI + lane / DC;
+            const int tok = min(tok0 + row, ctx - 1);                 // rows past the context re-read the last key
             const int pg = pt[tok >> a.page_shift];
-            const bf16* kp = a.K_pool + ((int64_t)pg * a.Hkv + hkv) * slab + (int64_t)(tok & page_mask) * D + half * 8;
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) kf[kvb][ks] = *(const bf16x8*)(kp + ks * 16);
+            const int64_t off = ((int64_t)pg * a.Hkv + hkv) * slab + (int64_t)(tok & page_mask) * D +
+                                (((lane % DC) ^ swz<D>(row)) * 8);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.K_pool + off),
+                                             (__attribute__((address_space(3))) void*)(k_tile + i * 512), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.V_pool + off),
+                                             (__attribute__((address_space(3))) void*)(v_tile + i * 512), 16, 0, 0);
         }
-        // ---- gather V: each lane takes units of 4 consecutive keys x 8 dims
-        u32x4 vreg[NVT][4];
-#pragma unroll
-        for (int i = 0; i < NVT; ++i) {
-            const int u = lane + i * 64, gq = u / DC, cc = u % DC;
-            const int tok = min(tok0 + 4 * gq, ((ctx - 1) >> 2) << 2);  // 4-key groups never straddle a page
-            const int pg = pt[tok >> a.page_shift];
-            const bf16* vp = a.V_pool + ((int64_t)pg * a.Hkv + hkv) * slab + (int64_t)(tok & page_mask) * D + cc * 8;
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) vreg[i][r4] = *(const u32x4*)(vp + r4 * D);
-        }
+        wait_vmem();
 
         // ---- S^T = K Q^T
-        f32x16 sacc[2];
+        f32x16 sacc;
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb) {
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kvb][r] = 0.0f;
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) sacc[kvb] = mfma32(kf[kvb][ks], qf[ks], sacc[kvb]);
-        }
-
-        // ---- V^T into the wave's LDS tile
-#pragma unroll
-        for (int i = 0; i < NVT; ++i) {
-            const int u = lane + i * 64, gq = u / DC, cc = u % DC;
-            const int pos = 16 * (gq >> 2) + dec_vt_pos16(4 * (gq & 3));
-#pragma unroll
-            for (int wd = 0; wd < 4; ++wd) {
-                const uint32_t r0 = vreg[i][0][wd], r1 = vreg[i][1][wd], r2 = vreg[i][2][wd], r3 = vreg[i][3][wd];
-                u32x2 lo, hi;
-                lo[0] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);
-                lo[1] = __builtin_amdgcn_perm(r3, r2, 0x05040100u);
-                hi[0] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);
-                hi[1] = __builtin_amdgcn_perm(r3, r2, 0x07060302u);
-                *(u32x2*)(&Vt[(cc * 8 + 2 * wd) * VS + pos]) = lo;
-                *(u32x2*)(&Vt[(cc * 8 + 2 * wd + 1) * VS + pos]) = hi;
-            }
-        }
+        for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(k_reader.read(0, 0, ks), qf[ks], sacc);
 
         // ---- score_mod, mask kv < ctx_len (only the last tile can hold masked keys), softmax
         const bool ragged = tok0 + kDecTile > tok_end;
         float mx = -INFINITY;
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kv = tok0 + kvb * 32 + crow(r, half);
-                float x = smod.apply(sacc[kvb][r], q_idx - kv);
-                if (ragged && kv >= tok_end) x = -INFINITY;
-                sacc[kvb][r] = x;
-                mx = fmaxf(mx, x);
-            }
+        for (int r = 0; r < 16; ++r) {
+            const int kv = tok0 + crow(r, half);
+            float x = smod.apply(sacc[r], q_idx - kv);
+            if (ragged && kv >= tok_end) x = -INFINITY;
+            sacc[r] = x;
+            mx = fmaxf(mx, x);
+        }
         mx = fmaxf(mx, swap_halves(mx));
-        const float m_new = fmaxf(m_run, mx);          // finite: every split holds at least one key
+        const float m_new = fmaxf(m_run, mx);          // finite: every tile holds at least one key
         const float alpha = fast_exp2(m_run - m_new);
         m_run = m_new;
         float psum = 0.0f;
-        bf16x8 pf[2][2];
+        bf16x8 pf[2];
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb)
+        for (int c = 0; c < 2; ++c) {
+            u32x4 pk;
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                u32x4 pk;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const float p0 = fast_exp2(sacc[kvb][8 * c + 2 * jj] - m_new);
-                    const float p1 = fast_exp2(sacc[kvb][8 * c + 2 * jj + 1] - m_new);
-                    psum += p0 + p1;
-                    pk[jj] = pack_bf16(p0, p1);
-                }
-                pf[kvb][c] = __builtin_bit_cast(bf16x8, pk);
+            for (int jj = 0; jj < 4; ++jj) {
+                const float p0 = fast_exp2(sacc[8 * c + 2 * jj] - m_new);
+                const float p1 = fast_exp2(sacc[8 * c + 2 * jj + 1] - m_new);
+                psum += p0 + p1;
+                pk[jj] = pack_bf16(p0, p1);
             }
+            pf[c] = __builtin_bit_cast(bf16x8, pk);
+        }
         l_run = l_run * alpha + psum;
+        if (__any(alpha != 1.0f)) {
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+            for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        }
 
-        // ---- O^T += V^T P^T  (LDS writes above are ordered before these reads within the wave)
-        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+        // ---- O^T += V^T P^T
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const bf16x8 vf = *(const bf16x8*)(&Vt[(db * 32 + l32) * VS + (kvb * 2 + c) * 16 + half * 8]);
-                    oacc[db] = mfma32(vf, pf[kvb][c], oacc[db]);
-                }
+            for (int c = 0; c < 2; ++c) oacc[db] = mfma32(v_reader.read(0, 16 * c, db), pf[c], oacc[db]);
     }
 
     const float l_tot = l_run + swap_halves(l_run);
