@@ -92,7 +92,10 @@ typedef struct flexattn_mod_params {
     const int32_t* ctx_lens;      /* CTX_LEN: [B] int32                                        */
 } flexattn_mod_params;
 
-/* A 4-D tensor [batch, head, seq, D] with unit stride in D. */
+/* A 4-D tensor [batch, head, seq, D] with unit stride in D.  ptr is 16-byte aligned, the
+ * strides are multiples of 8 elements, stride_s >= D, and one (batch, head) slice spans less
+ * than 2 GiB ((seq_len - 1) * stride_s + D elements): rows are addressed with 32-bit offsets.
+ * A larger slice is refused with FLEXATTN_ERR_UNSUPPORTED. */
 typedef struct flexattn_tensor {
     void*   ptr;
     int64_t stride_b, stride_h, stride_s;   /* in elements */

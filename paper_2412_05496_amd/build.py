@@ -24,7 +24,8 @@ NUM_VARIANTS = 9          # must equal kNumVariants in csrc/variants.h
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Wno-unused-result", "-Wno-pass-failed",
          # packed-fp32 VALU forms are not to be generated on the test machines
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         *os.environ.get("FLEXATTN_EXTRA_FLAGS", "").split()]
 
 
 def _units():

@@ -12,6 +12,7 @@ static const BwdLauncher kBwdLaunchers[kNumVariants] = {bwd_launch_0, bwd_launch
                                                         bwd_launch_3, bwd_launch_4, bwd_launch_5,
                                                         bwd_launch_6, bwd_launch_7, bwd_launch_8};
 int check_tensor(const flexattn_tensor* t);
+int check_extent(const flexattn_tensor* t, int len, int D);
 int check_problem(const flexattn_dims* d, const flexattn_blockmask* bm);
 
 }  // namespace flexattn
@@ -39,6 +40,8 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
     if ((stages & FLEXATTN_BWD_DQ) && (rc = check_tensor(dQ)) != FLEXATTN_OK) return rc;
     if ((stages & FLEXATTN_BWD_DKDV) && ((rc = check_tensor(dK)) != FLEXATTN_OK || (rc = check_tensor(dV)) != FLEXATTN_OK))
         return rc;
+    if ((rc = check_extent(Q, dims->q_len, dims->D)) != FLEXATTN_OK) return rc;
+    if ((rc = check_extent(dO, dims->q_len, dims->D)) != FLEXATTN_OK) return rc;
     static const flexattn_tensor kNoTensor = {nullptr, 0, 0, 0};
     if (!(stages & FLEXATTN_BWD_DQ)) dQ = &kNoTensor;
     if (!(stages & FLEXATTN_BWD_DKDV)) dK = dV = &kNoTensor;
@@ -76,17 +79,10 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
     if (params) a.p = *params;
 
     hipStream_t st = (hipStream_t)stream;
-    if (stages & FLEXATTN_BWD_DELTA) {
-        if (dims->D == 128) {
-            hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
-        } else {
-            hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, a);
-        }
-    }
-    if (stages & (FLEXATTN_BWD_DKDV | FLEXATTN_BWD_DQ)) {
-        rc = kBwdLaunchers[vi](a, dims->D, stages, st);
-        if (rc != FLEXATTN_OK) return rc;
-    }
+    const uint32_t delta_stage = stages & FLEXATTN_BWD_DELTA;
+    (void)delta_stage;
+    rc = kBwdLaunchers[vi](a, dims->D, stages, st);     // the delta pre-pass depends on the score_mod too
+    if (rc != FLEXATTN_OK) return rc;
     FLEXATTN_HIP_TRY(hipGetLastError());
     return FLEXATTN_OK;
 }

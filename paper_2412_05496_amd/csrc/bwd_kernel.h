@@ -34,8 +34,8 @@ struct BwdArgs {
     bf16* dQ;
     bf16* dK;
     bf16* dV;
-    float* delta;   // [B, Hq, q_len]
-    float* lse2;    // [B, Hq, q_len]  LSE * log2(e); +inf for rows with every key masked
+    float* delta;   // [B, Hq, q_len]  MINUS rowsum(dO * O): the dP accumulators start from it
+    float* lse2;    // [B, Hq, q_len]  row constant rc of ScoreMod::p_with_grad (from LSE); -inf for dead rows
     int64_t q_sb, q_sh, q_ss, k_sb, k_sh, k_ss, v_sb, v_sh, v_ss, o_sb, o_sh, o_ss, do_sb, do_sh, do_ss;
     int64_t dq_sb, dq_sh, dq_ss, dk_sb, dk_sh, dk_ss, dv_sb, dv_sh, dv_ss;
     int B, Hq, Hkv, G, q_len, kv_len;
@@ -54,7 +54,10 @@ struct BwdArgs {
 };
 
 // ------------------------------------------------------------------------------------------
-template <int D>
+// -delta = -rowsum(dO * O) and the per-row constant rc of ScoreMod::p_with_grad (so that the main
+// kernels get P = exp2(f(score) + rc) with no further per-row arithmetic); rc = -inf for rows
+// without a visible key (LSE = -inf), which makes their P vanish.
+template <int D, uint32_t SCORE>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const BwdArgs a) {
     // 8 lanes per row (D = 64) or 16 lanes per row (D = 128): each lane owns 8 consecutive dims.
     constexpr int LPR = D / 8;
@@ -74,26 +77,69 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const BwdArgs a) {
 #pragma unroll
     for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if (c == 0) {
-        a.delta[row] = s;
+        a.delta[row] = -s;
         const float l = a.LSE[row];
-        a.lse2[row] = (l == -INFINITY) ? INFINITY : l * kLog2e;
+        const ScoreMod<SCORE> smod(a.p, h, a.scale);
+        a.lse2[row] = smod.row_const((l == -INFINITY) ? INFINITY : l * kLog2e);
     }
 }
 
+// Issue order of the MFMAs of one dK/dV step (see bwd_dkdv_kernel).  MFMA ids: [0, N1) are S / dP
+// of the next step (alternating, k-slice id / 2); N1 + c * N3H + j are dV^T (j even) / dK^T (j odd)
+// of this step for the 16-row slice c and output block j / 2.  Chunk i < 8 carries score elements
+// 2i, 2i+1; slice 0 needs elements 0..7 (chunks 0..3) and is issued in chunks 4..7, slice 1 needs
+// all sixteen and forms the four tail chunks.
+template <int D>
+struct DkdvSchedule {
+    static constexpr int N1 = D / 8, N3H = D / 16, NM = N1 + 2 * N3H, NCHUNK = 12;
+    int order[NM];
+    int begin[NCHUNK + 1];
+    static constexpr DkdvSchedule make() {
+        DkdvSchedule s{};
+        int n = 0;
+        for (int i = 0; i < NCHUNK; ++i) {
+            s.begin[i] = n;
+            if (i < 8)
+                for (int m = i * N1 / 8; m < (i + 1) * N1 / 8; ++m) s.order[n++] = m;
+            if (i >= 4 && i < 8)
+                for (int m = (i - 4) * N3H / 4; m < (i - 3) * N3H / 4; ++m) s.order[n++] = N1 + m;
+            if (i >= 8)
+                for (int m = (i - 8) * N3H / 4; m < (i - 7) * N3H / 4; ++m) s.order[n++] = N1 + N3H + m;
+        }
+        s.begin[NCHUNK] = n;
+        return s;
+    }
+};
+
 // ------------------------------------------------------------------------------------------
-// dK, dV.  256 threads = 4 waves; one workgroup per 64 keys.  The listed q-blocks are walked in
-// steps of two 64-row half-tiles; wave w owns keys 32 * (w & 1) .. +32 and the half-tile w >> 1,
-// which it processes as two 32 x 32 score blocks so that the MFMAs of one block sit next to the
-// exp / dS arithmetic of the other.  The two waves that share keys add their accumulators
-// through LDS at the end.
+// dK, dV.  256 threads = 4 waves, one workgroup per 64 keys, one wave per SIMD (the accumulators
+// need the whole register file).  The listed q-blocks are walked in steps of 64 query rows; wave w
+// owns keys 32 * (w & 1) .. +32 and rows 32 * (w >> 1) .. +32 of every step, i.e. one 32 x 32
+// score block per step, and the two waves that share keys add their accumulators through LDS at
+// the end.
+//
+// A single wave per SIMD pays for every instruction it issues and for every dependent pair of
+// vector instructions, so the step is kept short and is written as an explicit software pipeline:
+// chunks of (MFMAs, the LDS operand reads for a later chunk, the exp / dS arithmetic of two score
+// elements, interleaved) separated by scheduling barriers.  In step v the matrix pipe runs S and
+// dP of step v+1 and dV^T, dK^T of step v while the vector pipe turns S, dP of step v into P and
+// dS.  dP accumulates on top of -delta, so dP - delta costs nothing.  Q / dO tiles and the
+// per-row scalars sit in a ring of four LDS buffers filled by buffer loads issued three steps
+// ahead (scalar row offset, constant per-lane offsets); one barrier per step.
 template <int D, uint32_t MASK, uint32_t SCORE>
 __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
-    constexpr int HQ = 64;                         // query rows per half-tile
-    constexpr int TILE = HQ * D;                   // elements per LDS tile
-    // per buffer: Q half a, Q half b, dO half a, dO half b; two buffers; reused for the final reduction
-    __shared__ __attribute__((aligned(1024))) bf16 smem[8 * TILE];
-    __shared__ __attribute__((aligned(16))) float s_row[2][2][2 * HQ];   // [buffer][lse2 | delta][row]
-    static_assert(sizeof(bf16) * 8 * TILE >= sizeof(float) * 4 * D * 32, "reduction buffer must fit");
+    constexpr int TQ = 64;                         // query rows per step
+    constexpr int TILE = TQ * D;                   // elements per LDS tile
+    constexpr int NBUF = 4;
+    constexpr int NKS = D / 16, NDB = D / 32;
+    using Loader = WaveTileLoader<D>;
+    constexpr int kLoads = 2 * Loader::NI + 1;     // buffer loads per wave and step
+    constexpr int kWaitOlder = 0x0F70 | kLoads;    // s_waitcnt vmcnt(kLoads): all but the newest step
+    static_assert(kLoads <= 15, "vmcnt immediate");
+    // ring of NBUF x (Q tile, dO tile); reused for the final reduction
+    __shared__ __attribute__((aligned(1024))) bf16 smem[NBUF * 2 * TILE];
+    __shared__ __attribute__((aligned(256))) float s_row[NBUF][2][TQ];   // [buffer][rc | -delta][row]
+    static_assert(sizeof(bf16) * NBUF * 2 * TILE >= sizeof(float) * 4 * D * 32, "reduction buffer must fit");
 
     // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
     const int units = a.B * a.Hkv;
@@ -106,37 +152,44 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
     const int kv0 = tile * 64;
     const int col = kv0 / a.Bk;         // column of BlockMask blocks this tile lies in
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb = w & 1, qh = w >> 1;
     const int kv_lane = kv0 + 32 * kb + l32;
 
     // K, V fragments of this wave's 32 keys: B operands (column = key, k-slots = dims)
-    bf16x8 kf[D / 16], vf[D / 16];
+    bf16x8 kf[NKS], vf[NKS];
     {
         const bf16* kp = a.K + b * a.k_sb + hkv * a.k_sh + (int64_t)kv_lane * a.k_ss + half * 8;
         const bf16* vp = a.V + b * a.v_sb + hkv * a.v_sh + (int64_t)kv_lane * a.v_ss + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
+        for (int ks = 0; ks < NKS; ++ks) {
             kf[ks] = *(const bf16x8*)(kp + ks * 16);
             vf[ks] = *(const bf16x8*)(vp + ks * 16);
         }
     }
 
-    f32x16 dk[D / 32], dv[D / 32];
+    f32x16 dk[NDB], dv[NDB];
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             dk[db][r] = 0.0f;
             dv[db][r] = 0.0f;
         }
 
-    const int sub = a.Bq / HQ;          // half-tiles per BlockMask row block
-    const TileLoader<D, 4> q_loader(a.q_ss, w, lane), do_loader(a.do_ss, w, lane);
-    // per-lane LDS addresses of this wave's half-tile (Q copy; the dO copy is 2 tiles further on)
-    const uint32_t my_tile = lds_addr(smem) + qh * (TILE * 2);
-    const RowReader<D> row_reader(l32, half, my_tile);
-    const TrReader<D> tr_reader(lane, my_tile);
+    const int sub = a.Bq / TQ;          // steps per BlockMask row block
+    const Loader q_loader(a.q_ss, w, lane), do_loader(a.do_ss, w, lane);
+    const uint32_t wave_q = lds_addr(smem) + w * (Loader::NI * 1024);    // this wave's part of Q tile 0
+    const uint32_t wave_row = lds_addr(&s_row[0][w & 1][0]);
+    const uint32_t q_bytes = (uint32_t)((a.q_len - 1) * a.q_ss + D) * 2u;
+    const uint32_t do_bytes = (uint32_t)((a.q_len - 1) * a.do_ss + D) * 2u;
+    const int q_row_bytes = (int)a.q_ss * 2, do_row_bytes = (int)a.do_ss * 2;
+    // per-lane LDS addresses of this wave's 32 rows inside buffer 0 (Q copy; dO is one tile further)
+    const uint32_t my_rows = lds_addr(smem) + qh * 32 * D * 2;
+    const RowReader<D> row_reader(l32, half, my_rows);
+    const TrReader<D> tr_reader(lane, my_rows);
+    const uint32_t row_lds = lds_addr(&s_row[0][0][0]) + (32 * qh + 4 * half) * 4;
 
     for (int g = 0; g < a.G; ++g) {
         const int hq = hkv * a.G + g;
@@ -144,135 +197,184 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
         const int n_full = a.full_q_num[line], n_part = a.q_num[line];
         const int32_t* full_idx = a.full_q_idx + line * a.NR;
         const int32_t* part_idx = a.q_idx + line * a.NR;
-        const int H = (n_full + n_part) * sub;      // half-tiles to visit
+        const int H = (n_full + n_part) * sub;      // steps
         if (H == 0) continue;
-        const int U = (H + 1) / 2;                  // steps
-        const bf16* q_base = a.Q + b * a.q_sb + hq * a.q_sh;
-        const bf16* do_base = a.dO + b * a.do_sb + hq * a.do_sh;
-        const float* lse_base = a.lse2 + ((int64_t)b * a.Hq + hq) * a.q_len;
-        const float* delta_base = a.delta + ((int64_t)b * a.Hq + hq) * a.q_len;
+        const __amdgpu_buffer_rsrc_t q_rsrc = make_rsrc(a.Q + b * a.q_sb + hq * a.q_sh, q_bytes);
+        const __amdgpu_buffer_rsrc_t do_rsrc = make_rsrc(a.dO + b * a.do_sb + hq * a.do_sh, do_bytes);
+        // waves 0, 2 fetch the rc row, waves 1, 3 the -delta row (the duplicates write the same values)
+        const __amdgpu_buffer_rsrc_t row_rsrc =
+            make_rsrc(((w & 1) ? a.delta : a.lse2) + ((int64_t)b * a.Hq + hq) * a.q_len, (uint32_t)a.q_len * 4u);
         const ScoreMod<SCORE> smod(a.p, hq, a.scale);
 
-        auto half_q0 = [&](int h) {                 // first query row of half-tile h (h < H)
-            const int pos = h / sub, s = h - pos * sub;
-            const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
-            return blk * a.Bq + s * HQ;
-        };
-        // starts the loads of step u into buffer u & 1; returns this thread's row scalar
-        auto load_step = [&](int u) {
-            bf16* buf = smem + (u & 1) * 4 * TILE;
-            const int qa = half_q0(2 * u);
-            const bool has_b = 2 * u + 1 < H;
-            const int qb = has_b ? half_q0(2 * u + 1) : qa;
-            // row scalars first: waiting for them later must not wait for the tiles behind them
-            const int rr = tid & (2 * HQ - 1);
-            const int qrow = (rr < HQ ? qa : qb) + (rr & (HQ - 1));
-            const float v = tid < 2 * HQ ? lse_base[qrow] : delta_base[qrow];
-            q_loader.start(buf, q_base + (int64_t)qa * a.q_ss);
-            do_loader.start(buf + 2 * TILE, do_base + (int64_t)qa * a.do_ss);
-            if (has_b) {
-                q_loader.start(buf + TILE, q_base + (int64_t)qb * a.q_ss);
-                do_loader.start(buf + 3 * TILE, do_base + (int64_t)qb * a.do_ss);
+        // The merged list (FULL blocks, then PARTIAL ones) is walked from its END, one block index
+        // fetched ahead of its use.  ld_* describe the step whose loads are issued next.
+        auto block_at = [&](int pos) { return pos < n_full ? full_idx[pos] : part_idx[pos - n_full]; };
+        int ld_pos = n_full + n_part - 1, ld_s = sub - 1;
+        int blk_cur = block_at(ld_pos);
+        int blk_nxt = ld_pos > 0 ? block_at(ld_pos - 1) : 0;
+        int q0_of[NBUF];                            // first query row of the step in each ring slot,
+        bool part_of[NBUF];                         // and whether its block is PARTIAL
+
+        // Starts the loads of the next step into ring slot SLOT: exactly kLoads instructions per wave
+        // (the wait counts rely on it).
+        auto load_step = [&](auto slot_tag) {
+            constexpr int SLOT = decltype(slot_tag)::value;
+            const int q0 = blk_cur * a.Bq + ld_s * TQ;
+            q0_of[SLOT] = q0;
+            part_of[SLOT] = ld_pos >= n_full;
+            q_loader.start(q_rsrc, wave_q + SLOT * 2 * (TILE * 2), q0 * q_row_bytes);
+            do_loader.start(do_rsrc, wave_q + (SLOT * 2 + 1) * (TILE * 2), q0 * do_row_bytes);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                row_rsrc, (__attribute__((address_space(3))) void*)(uintptr_t)(wave_row + SLOT * 2 * TQ * 4), 4,
+                lane * 4, q0 * 4, 0, 0);
+            if (--ld_s < 0) {
+                ld_s = sub - 1;
+                --ld_pos;
+                blk_cur = blk_nxt;
+                blk_nxt = ld_pos > 0 ? block_at(ld_pos - 1) : 0;
             }
-            return v;
         };
-        // lse2 is stored as the row constant of ScoreMod::p_with_grad
-        auto store_rows = [&](int u, float v) {
-            s_row[u & 1][tid >> 7][tid & (2 * HQ - 1)] = tid < 2 * HQ ? smod.row_const(v) : v;
+        // this lane's 16 row scalars of a step: rows 8 rg + 4 half + {0..3} of the wave's 32
+        auto read_rows = [&](int slot, int which, f32x4 (&out)[4]) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg)
+                out[rg] = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(
+                    row_lds + (uint32_t)((slot * 2 + which) * TQ + 8 * rg) * 4);
+        };
+        auto as_acc = [](const f32x4 (&v)[4]) {
+            f32x16 o;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[r] = v[r >> 2][r & 3];
+            return o;
         };
 
-        store_rows(0, load_step(0));
-        wait_vmem();
+        f32x16 s_even, dp_even, s_odd, dp_odd;      // S, dP - delta of even / odd steps
+        f32x4 rc_cur[4];
+
+        // ---- prologue: steps 0 and 1 in flight, S and dP of step 0
+        load_step(std::integral_constant<int, 0>{});
+        if (H > 1) load_step(std::integral_constant<int, 1>{});
+        if (H > 1) __builtin_amdgcn_s_waitcnt(kWaitOlder); else wait_vmem();      // step 0 has landed
         __syncthreads();
-
-        // One step on buffer BUF (compile-time, so that every LDS read is "VGPR + immediate").
-        auto step = [&](int u, auto buf_tag) {
-            constexpr int BUF = decltype(buf_tag)::value;
-            float row_next = 0.0f;
-            if (u + 1 < U) row_next = load_step(u + 1);     // buffer BUF ^ 1 was last read in step u-1
-            const int h_mine = 2 * u + qh;
-            if (h_mine < H) {
-                const int q0 = half_q0(h_mine);
-                const bool partial = (h_mine / sub) >= n_full;
-                constexpr uint32_t qt = BUF * 4 * (TILE * 2), dot = (BUF * 4 + 2) * (TILE * 2);
-                const float* lrow = &s_row[BUF][0][HQ * qh];
-                const float* drow = &s_row[BUF][1][HQ * qh];
-
-                // S = Q K^T and dP = dO V^T for both 32-row blocks of this wave
-                f32x16 sacc[2], dpacc[2];
+        if (H > 2) load_step(std::integral_constant<int, 2>{});
+        {
+            f32x4 nd[4];
+            read_rows(0, 1, nd);
+            dp_even = as_acc(nd);
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
+            for (int r = 0; r < 16; ++r) s_even[r] = 0.0f;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        sacc[j][r] = 0.0f;
-                        dpacc[j][r] = 0.0f;
-                    }
-#pragma unroll
-                    for (int ks = 0; ks < D / 16; ++ks) sacc[j] = mfma32(row_reader.read(qt, 32 * j, ks), kf[ks], sacc[j]);
-#pragma unroll
-                    for (int ks = 0; ks < D / 16; ++ks) dpacc[j] = mfma32(row_reader.read(dot, 32 * j, ks), vf[ks], dpacc[j]);
-                }
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    // P = exp2(x - lse2), dS = P * (dP - delta) * g; row = 32 j + crow(r, half)
-                    f32x4 rc4[4], del4[4];
-#pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        rc4[rg] = *(const f32x4*)(lrow + 32 * j + 8 * rg + 4 * half);
-                        del4[rg] = *(const f32x4*)(drow + 32 * j + 8 * rg + 4 * half);
-                    }
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int qi = q0 + 32 * j + crow(r, half);
-                        float gr;
-                        const float pe = smod.p_with_grad(sacc[j][r], qi - kv_lane, rc4[r >> 2][r & 3], gr);
-                        sacc[j][r] = pe;
-                        dpacc[j][r] = pe * (dpacc[j][r] - del4[r >> 2][r & 3]) * gr;
-                    }
-                    if (partial) {
-                        asm volatile("" ::: "memory");   // keep this a branch
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const MaskRow<MASK> mrow(a.p, b, hq, q0 + 32 * j + crow(r, half));
-                            const bool keep = mrow(kv_lane);
-                            sacc[j][r] = keep ? sacc[j][r] : 0.0f;
-                            dpacc[j][r] = keep ? dpacc[j][r] : 0.0f;
-                        }
-                    }
-                    // dV^T += dO^T P, dK^T += Q^T dS  (contraction over these 32 query rows)
-#pragma unroll
-                    for (int c = 0; c < 2; ++c) {
-                        u32x4 pk, dsk;
-#pragma unroll
-                        for (int jj = 0; jj < 4; ++jj) {
-                            pk[jj] = pack_bf16(sacc[j][8 * c + 2 * jj], sacc[j][8 * c + 2 * jj + 1]);
-                            dsk[jj] = pack_bf16(dpacc[j][8 * c + 2 * jj], dpacc[j][8 * c + 2 * jj + 1]);
-                        }
-#pragma unroll
-                        for (int db = 0; db < D / 32; ++db) {
-                            dv[db] = mfma32(tr_reader.read(dot, 32 * j + 16 * c, db), __builtin_bit_cast(bf16x8, pk), dv[db]);
-                            dk[db] = mfma32(tr_reader.read(qt, 32 * j + 16 * c, db), __builtin_bit_cast(bf16x8, dsk), dk[db]);
-                        }
-                    }
-                }
+            for (int ks = 0; ks < NKS; ++ks) {
+                s_even = mfma32(row_reader.read(0, 0, ks), kf[ks], s_even);
+                dp_even = mfma32(row_reader.read(TILE * 2, 0, ks), vf[ks], dp_even);
             }
-            if (u + 1 < U) store_rows(u + 1, row_next);
-            wait_vmem();
-            __syncthreads();
-        };
-        int u = 0;
-        for (; u + 1 < U; u += 2) {
-            step(u, std::integral_constant<int, 0>{});
-            step(u + 1, std::integral_constant<int, 1>{});
+            read_rows(0, 0, rc_cur);
         }
-        if (u < U) step(u, std::integral_constant<int, 0>{});
+
+        // ---- one step; SLOT = v % NBUF is compile-time so that every LDS access is "VGPR + immediate"
+        auto step = [&](int v, auto slot_tag) {
+            constexpr int SLOT = decltype(slot_tag)::value;
+            constexpr int NEXT = (SLOT + 1) & (NBUF - 1);
+            constexpr uint32_t q_cur = SLOT * 2 * (TILE * 2), do_cur = q_cur + TILE * 2;
+            constexpr uint32_t q_nxt = NEXT * 2 * (TILE * 2), do_nxt = q_nxt + TILE * 2;
+            f32x16& sacc = (SLOT & 1) ? s_odd : s_even;
+            f32x16& dpacc = (SLOT & 1) ? dp_odd : dp_even;
+            f32x16& s_nxt = (SLOT & 1) ? s_even : s_odd;
+            f32x16& dp_nxt = (SLOT & 1) ? dp_even : dp_odd;
+
+            // Step v+1 must have landed (it is read below), step v+2 may still be in flight; after the
+            // barrier nobody reads step v-1 any more and its slot takes step v+3.
+            if (v + 2 < H) __builtin_amdgcn_s_waitcnt(kWaitOlder); else wait_vmem();
+            __syncthreads();
+            f32x4 nd[4];
+            read_rows(NEXT, 1, nd);                  // -delta of step v+1: dP starts from it
+            if (v + 3 < H) load_step(std::integral_constant<int, (SLOT + 3) & (NBUF - 1)>{});
+            const bool partial = part_of[SLOT];
+            const int q_first = q0_of[SLOT] + 32 * qh;
+
+            u32x4 pk[2], dsk[2];
+            auto element_pair = [&](int e) {
+                float pe[2], ds[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int r = 2 * e + i;
+                    float gr;
+                    // alibi / rel-bias need q - kv; the soft-cap and the plain score do not
+                    const int dqk = (ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel) ? q_first + crow(r, half) - kv_lane : 0;
+                    pe[i] = smod.p_with_grad(sacc[r], dqk, rc_cur[r >> 2][r & 3], gr);
+                    ds[i] = pe[i] * gr * dpacc[r];
+                }
+                if (partial) {
+                    asm volatile("" ::: "memory");   // keep this a (scalar, rarely taken) branch
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const MaskRow<MASK> mrow(a.p, b, hq, q_first + crow(2 * e + i, half));
+                        const bool keep = mrow(kv_lane);
+                        pe[i] = keep ? pe[i] : 0.0f;
+                        ds[i] = keep ? ds[i] : 0.0f;
+                    }
+                }
+                pk[e >> 2][e & 3] = pack_bf16(pe[0], pe[1]);
+                dsk[e >> 2][e & 3] = pack_bf16(ds[0], ds[1]);
+            };
+            constexpr int N1 = 2 * NKS, N3H = 2 * NDB, NM = N1 + 2 * N3H;
+            auto frag_load = [&](int m) {
+                if (m < N1) return (m & 1) ? row_reader.read(do_nxt, 0, m >> 1) : row_reader.read(q_nxt, 0, m >> 1);
+                const int j = m - N1, c = j / N3H, jj = j % N3H;
+                return (jj & 1) ? tr_reader.read(q_cur, 16 * c, jj >> 1) : tr_reader.read(do_cur, 16 * c, jj >> 1);
+            };
+            auto mfma_op = [&](int m, bf16x8 fr) {
+                if (m < N1) {
+                    if (m == 0) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) s_nxt[r] = 0.0f;
+                    }
+                    if (m == 1) dp_nxt = as_acc(nd);
+                    if (m & 1) dp_nxt = mfma32(fr, vf[m >> 1], dp_nxt);
+                    else s_nxt = mfma32(fr, kf[m >> 1], s_nxt);
+                } else {
+                    const int j = m - N1, c = j / N3H, jj = j % N3H;
+                    if (jj & 1) dk[jj >> 1] = mfma32(fr, __builtin_bit_cast(bf16x8, dsk[c]), dk[jj >> 1]);
+                    else dv[jj >> 1] = mfma32(fr, __builtin_bit_cast(bf16x8, pk[c]), dv[jj >> 1]);
+                }
+            };
+            constexpr int PF = 3;                    // operand fragments are read PF MFMAs ahead
+            constexpr DkdvSchedule<D> kSched = DkdvSchedule<D>::make();
+            bf16x8 fr[NM];
+#pragma unroll
+            for (int sq = 0; sq < PF; ++sq) fr[kSched.order[sq]] = frag_load(kSched.order[sq]);
+#pragma unroll
+            for (int i = 0; i < kSched.NCHUNK; ++i) {
+#pragma unroll
+                for (int sq = kSched.begin[i]; sq < kSched.begin[i + 1]; ++sq) {
+                    if (sq + PF < NM) fr[kSched.order[sq + PF]] = frag_load(kSched.order[sq + PF]);
+                    mfma_op(kSched.order[sq], fr[kSched.order[sq]]);
+                }
+                if (i < 8) element_pair(i);
+                if (i == kSched.NCHUNK - 1) read_rows(NEXT, 0, rc_cur);   // for the next step's elements
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+
+        int v = 0;
+        for (; v + 3 < H; v += 4) {
+            step(v, std::integral_constant<int, 0>{});
+            step(v + 1, std::integral_constant<int, 1>{});
+            step(v + 2, std::integral_constant<int, 2>{});
+            step(v + 3, std::integral_constant<int, 3>{});
+        }
+        if (v < H) step(v, std::integral_constant<int, 0>{});
+        if (v + 1 < H) step(v + 1, std::integral_constant<int, 1>{});
+        if (v + 2 < H) step(v + 2, std::integral_constant<int, 2>{});
+        wait_vmem();
+        __syncthreads();                // before the next head (or the reduction) reuses the ring
     }
 
     // ---- add the two query-halves through LDS and write dK, dV (bf16)
     float* red = (float*)smem;          // [key block][dK | dV][D][32 keys] floats
     if (qh == 1) {
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 red[((kb * 2 + 0) * D + db * 32 + crow(r, half)) * 32 + l32] = dk[db][r];
@@ -285,7 +387,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
         bf16* dkp = a.dK + b * a.dk_sb + hkv * a.dk_sh + (int64_t)kv_lane * a.dk_ss;
         bf16* dvp = a.dV + b * a.dv_sb + hkv * a.dv_sh + (int64_t)kv_lane * a.dv_ss;
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 float k4[4], v4[4];
@@ -351,7 +453,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
         }
     }
     const int64_t rowi = ((int64_t)b * a.Hq + hq) * a.q_len + q_row;
-    const float lse2 = a.lse2[rowi], delta = a.delta[rowi];
+    const float lse2 = a.lse2[rowi], neg_delta = a.delta[rowi];
     const bf16* k_base = a.K + b * a.k_sb + hkv * a.k_sh;
     const bf16* v_base = a.V + b * a.v_sb + hkv * a.v_sh;
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
@@ -369,7 +471,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     };
     const RowReader<D> row_reader(l32, half, lds_addr(smem));
     const TrReader<D> tr_reader(lane, lds_addr(smem));
-    const float rc = smod.row_const(lse2);
+    const float rc = lse2;                     // the delta kernel stored the row constant
 
     f32x16 dq[D / 32];
 #pragma unroll
@@ -411,7 +513,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
                 const int kv = kv0_cur + kvb * 32 + crow(r, half);
                 float gr;
                 const float pe = smod.p_with_grad(sacc[r], q_row - kv, rc, gr);
-                dpacc[r] = pe * (dpacc[r] - delta) * gr;
+                dpacc[r] = pe * (dpacc[r] + neg_delta) * gr;
             }
             if (partial) {
                 asm volatile("" ::: "memory");   // keep this a branch
@@ -459,6 +561,11 @@ int launch_bwd_variant(const BwdArgs& a, int D, uint32_t stages, hipStream_t st)
     const unsigned grid_kv = (unsigned)(((units + 7) / 8) * 8 * (a.kv_len / 64));
     const unsigned grid_q = (unsigned)(((units + 7) / 8) * 8 * a.G * a.NR);
     const bool kv = stages & FLEXATTN_BWD_DKDV, q = stages & FLEXATTN_BWD_DQ;
+    if (stages & FLEXATTN_BWD_DELTA) {
+        const size_t rows = (size_t)a.B * a.Hq * a.q_len;
+        if (D == 128) hipLaunchKernelGGL((bwd_delta_kernel<128, SCORE>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((bwd_delta_kernel<64, SCORE>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, a);
+    }
     if (D == 128) {
         if (kv) hipLaunchKernelGGL((bwd_dkdv_kernel<128, MASK, SCORE>), dim3(grid_kv), dim3(256), 0, st, a);
         if (q && a.Bq == 128) hipLaunchKernelGGL((bwd_dq_kernel<128, 4, MASK, SCORE>), dim3(grid_q), dim3(256), 0, st, a);

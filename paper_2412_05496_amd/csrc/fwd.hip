@@ -23,6 +23,13 @@ int check_tensor(const flexattn_tensor* t) {
     return FLEXATTN_OK;
 }
 
+// The kernels address the rows of one (b, h) slice with 32-bit byte offsets.
+int check_extent(const flexattn_tensor* t, int len, int D) {
+    if (t->stride_s < D) return FLEXATTN_ERR_INVALID_ARG;
+    const int64_t bytes = ((int64_t)(len - 1) * t->stride_s + D) * 2;
+    return bytes < ((int64_t)1 << 31) ? FLEXATTN_OK : FLEXATTN_ERR_UNSUPPORTED;
+}
+
 int check_problem(const flexattn_dims* d, const flexattn_blockmask* bm) {
     if (!d || !bm) return FLEXATTN_ERR_INVALID_ARG;
     if (d->B <= 0 || d->Hq <= 0 || d->Hkv <= 0 || d->q_len <= 0 || d->kv_len <= 0) return FLEXATTN_ERR_INVALID_ARG;

@@ -66,6 +66,43 @@ struct TileLoader {
     }
 };
 
+// Raw buffer resource over `bytes` bytes at `p`: loads beyond it return zero instead of faulting.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// The same tile copy with buffer loads (buffer_load_dwordx4 ... lds), for a workgroup of 4 waves:
+// the row of the tile is selected by a scalar byte offset, so starting a tile costs one M0 write
+// and NI loads and no vector arithmetic.  Wave w fills the contiguous LDS bytes
+// [w * 1024 * NI, (w + 1) * 1024 * NI) of the tile; the instruction's immediate offset moves the LDS
+// destination by 1 KiB per load and, because it is added to the memory address as well, is taken
+// out of the per-lane offsets again (they stay non-negative as long as the row stride is >= D).
+template <int D>
+struct WaveTileLoader {
+    static constexpr int DC = D / 8, RPI = 64 / DC, NI = D / 32;
+    int32_t voff[NI];                           // per-lane byte offsets
+    __device__ __forceinline__ WaveTileLoader(int64_t gs, int wave, int lane) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int row = (wave * NI + i) * RPI + lane / DC;
+            voff[i] = (int32_t)(row * gs * 2) + (((lane % DC) ^ swz<D>(row)) * 16) - i * 1024;
+        }
+    }
+    template <int I>
+    __device__ __forceinline__ void one(__amdgpu_buffer_rsrc_t rsrc, __attribute__((address_space(3))) void* dst,
+                                        int soff) const {
+        if constexpr (I < NI) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, voff[I], soff, I * 1024, 0);
+            one<I + 1>(rsrc, dst, soff);
+        }
+    }
+    // `wave_tile`: LDS byte address of this wave's part of the tile (wave-uniform);
+    // `soff`: byte offset of the tile's first row inside the resource (wave-uniform)
+    __device__ __forceinline__ void start(__amdgpu_buffer_rsrc_t rsrc, uint32_t wave_tile, int soff) const {
+        one<0>(rsrc, (__attribute__((address_space(3))) void*)(uintptr_t)wave_tile, soff);
+    }
+};
+
 // Row reads: fragment (row0 + lane % 32, dims 16 ks + 8 half ..) for row0 a multiple of 32.
 template <int D>
 struct RowReader {
