@@ -187,8 +187,15 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
     const int q_row_bytes = (int)a.q_ss * 2, do_row_bytes = (int)a.do_ss * 2;
     // per-lane LDS addresses of this wave's 32 rows inside buffer 0 (Q copy; dO is one tile further)
     const uint32_t my_rows = lds_addr(smem) + qh * 32 * D * 2;
-    const RowReader<D> row_reader(l32, half, my_rows);
-    const TrReader<D> tr_reader(lane, my_rows);
+    // (an LDS instruction's immediate offset reaches 64 KiB: one set of addresses per half of the ring)
+    const RowReader<D> row_reader_lo(l32, half, my_rows), row_reader_hi(l32, half, my_rows + 65536);
+    const TrReader<D> tr_reader_lo(lane, my_rows), tr_reader_hi(lane, my_rows + 65536);
+    auto read_row = [&](uint32_t tile_bytes, int row0, int ks) {
+        return tile_bytes < 65536 ? row_reader_lo.read(tile_bytes, row0, ks) : row_reader_hi.read(tile_bytes - 65536, row0, ks);
+    };
+    auto read_tr = [&](uint32_t tile_bytes, int r0, int cb) {
+        return tile_bytes < 65536 ? tr_reader_lo.read(tile_bytes, r0, cb) : tr_reader_hi.read(tile_bytes - 65536, r0, cb);
+    };
     const uint32_t row_lds = lds_addr(&s_row[0][0][0]) + (32 * qh + 4 * half) * 4;
 
     for (int g = 0; g < a.G; ++g) {
@@ -199,16 +206,16 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
         const int32_t* part_idx = a.q_idx + line * a.NR;
         const int H = (n_full + n_part) * sub;      // steps
         if (H == 0) continue;
-        const __amdgpu_buffer_rsrc_t q_rsrc = make_rsrc(a.Q + b * a.q_sb + hq * a.q_sh, q_bytes);
-        const __amdgpu_buffer_rsrc_t do_rsrc = make_rsrc(a.dO + b * a.do_sb + hq * a.do_sh, do_bytes);
+        const i32x4 q_rsrc = make_rsrc(a.Q + b * a.q_sb + hq * a.q_sh, q_bytes);
+        const i32x4 do_rsrc = make_rsrc(a.dO + b * a.do_sb + hq * a.do_sh, do_bytes);
         // waves 0, 2 fetch the rc row, waves 1, 3 the -delta row (the duplicates write the same values)
-        const __amdgpu_buffer_rsrc_t row_rsrc =
+        const i32x4 row_rsrc =
             make_rsrc(((w & 1) ? a.delta : a.lse2) + ((int64_t)b * a.Hq + hq) * a.q_len, (uint32_t)a.q_len * 4u);
         const ScoreMod<SCORE> smod(a.p, hq, a.scale);
 
         // The merged list (FULL blocks, then PARTIAL ones) is walked from its END, one block index
         // fetched ahead of its use.  ld_* describe the step whose loads are issued next.
-        auto block_at = [&](int pos) { return pos < n_full ? full_idx[pos] : part_idx[pos - n_full]; };
+        auto block_at = [&](int pos) { return pos < n_full ? ldc(full_idx + pos) : ldc(part_idx + (pos - n_full)); };
         int ld_pos = n_full + n_part - 1, ld_s = sub - 1;
         int blk_cur = block_at(ld_pos);
         int blk_nxt = ld_pos > 0 ? block_at(ld_pos - 1) : 0;
@@ -224,9 +231,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             part_of[SLOT] = ld_pos >= n_full;
             q_loader.start(q_rsrc, wave_q + SLOT * 2 * (TILE * 2), q0 * q_row_bytes);
             do_loader.start(do_rsrc, wave_q + (SLOT * 2 + 1) * (TILE * 2), q0 * do_row_bytes);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                row_rsrc, (__attribute__((address_space(3))) void*)(uintptr_t)(wave_row + SLOT * 2 * TQ * 4), 4,
-                lane * 4, q0 * 4, 0, 0);
+            dma_dword(row_rsrc, wave_row + SLOT * 2 * TQ * 4, lane * 4, q0 * 4);
             if (--ld_s < 0) {
                 ld_s = sub - 1;
                 --ld_pos;
@@ -265,8 +270,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             for (int r = 0; r < 16; ++r) s_even[r] = 0.0f;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                s_even = mfma32(row_reader.read(0, 0, ks), kf[ks], s_even);
-                dp_even = mfma32(row_reader.read(TILE * 2, 0, ks), vf[ks], dp_even);
+                s_even = mfma32(read_row(0, 0, ks), kf[ks], s_even);
+                dp_even = mfma32(read_row(TILE * 2, 0, ks), vf[ks], dp_even);
             }
             read_rows(0, 0, rc_cur);
         }
@@ -319,9 +324,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             };
             constexpr int N1 = 2 * NKS, N3H = 2 * NDB, NM = N1 + 2 * N3H;
             auto frag_load = [&](int m) {
-                if (m < N1) return (m & 1) ? row_reader.read(do_nxt, 0, m >> 1) : row_reader.read(q_nxt, 0, m >> 1);
+                if (m < N1) return (m & 1) ? read_row(do_nxt, 0, m >> 1) : read_row(q_nxt, 0, m >> 1);
                 const int j = m - N1, c = j / N3H, jj = j % N3H;
-                return (jj & 1) ? tr_reader.read(q_cur, 16 * c, jj >> 1) : tr_reader.read(do_cur, 16 * c, jj >> 1);
+                return (jj & 1) ? read_tr(q_cur, 16 * c, jj >> 1) : read_tr(do_cur, 16 * c, jj >> 1);
             };
             auto mfma_op = [&](int m, bf16x8 fr) {
                 if (m < N1) {

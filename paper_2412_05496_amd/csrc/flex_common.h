@@ -33,6 +33,12 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // Row of the 32x32 result tile held in register r by a lane of half `half` (= lane / 32).
 __device__ __forceinline__ constexpr int crow(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
+// Load of read-only data at a wave-uniform address: constant address space, so the compiler may
+// use the scalar cache and keep the load off the vector memory counter.
+__device__ __forceinline__ int32_t ldc(const int32_t* p) {
+    return *(const __attribute__((address_space(4))) int32_t*)(uintptr_t)p;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }

@@ -66,20 +66,36 @@ struct TileLoader {
     }
 };
 
-// Raw buffer resource over `bytes` bytes at `p`: loads beyond it return zero instead of faulting.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+// Raw buffer resource (four scalar dwords) over `bytes` bytes at `p`: no stride, loads beyond
+// the end return zero instead of faulting.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4 make_rsrc(const void* p, uint32_t bytes) {
+    const uint64_t addr = (uint64_t)p;
+    return i32x4{(int)(uint32_t)addr, (int)((uint32_t)(addr >> 32) & 0xffffu), (int)bytes, 0x00020000};
 }
 
-// The same tile copy with buffer loads (buffer_load_dwordx4 ... lds), for a workgroup of 4 waves:
-// the row of the tile is selected by a scalar byte offset, so starting a tile costs one M0 write
-// and NI loads and no vector arithmetic.  Wave w fills the contiguous LDS bytes
+// LDS-DMA loads are issued from inline assembly on purpose.  When the compiler sees such a load it
+// makes every later LDS read that it cannot prove disjoint wait for vmcnt(0), which serialises the
+// prefetch with the compute it is meant to overlap; completion is tracked by hand instead
+// (s_waitcnt vmcnt + barrier before a buffer is read).  s_nop 4 covers the wait states between a
+// write of M0 (or of a scalar operand by a vector instruction) and the loads that use it.
+//
+// dma_dword: 64 lanes x 4 bytes to `lds` .. +256.
+__device__ __forceinline__ void dma_dword(i32x4 rsrc, uint32_t lds, int voff, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+
+// The tile copy with buffer loads (buffer_load_dwordx4 ... lds), for a workgroup of 4 waves: the
+// row of the tile is selected by a scalar byte offset, so starting a tile costs one M0 write and
+// NI loads and no vector arithmetic.  Wave w fills the contiguous LDS bytes
 // [w * 1024 * NI, (w + 1) * 1024 * NI) of the tile; the instruction's immediate offset moves the LDS
 // destination by 1 KiB per load and, because it is added to the memory address as well, is taken
 // out of the per-lane offsets again (they stay non-negative as long as the row stride is >= D).
 template <int D>
 struct WaveTileLoader {
     static constexpr int DC = D / 8, RPI = 64 / DC, NI = D / 32;
+    static_assert(NI == 2 || NI == 4, "D is 64 or 128");
     int32_t voff[NI];                           // per-lane byte offsets
     __device__ __forceinline__ WaveTileLoader(int64_t gs, int wave, int lane) {
 #pragma unroll
@@ -88,18 +104,23 @@ struct WaveTileLoader {
             voff[i] = (int32_t)(row * gs * 2) + (((lane % DC) ^ swz<D>(row)) * 16) - i * 1024;
         }
     }
-    template <int I>
-    __device__ __forceinline__ void one(__amdgpu_buffer_rsrc_t rsrc, __attribute__((address_space(3))) void* dst,
-                                        int soff) const {
-        if constexpr (I < NI) {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, voff[I], soff, I * 1024, 0);
-            one<I + 1>(rsrc, dst, soff);
-        }
-    }
     // `wave_tile`: LDS byte address of this wave's part of the tile (wave-uniform);
     // `soff`: byte offset of the tile's first row inside the resource (wave-uniform)
-    __device__ __forceinline__ void start(__amdgpu_buffer_rsrc_t rsrc, uint32_t wave_tile, int soff) const {
-        one<0>(rsrc, (__attribute__((address_space(3))) void*)(uintptr_t)wave_tile, soff);
+    __device__ __forceinline__ void start(i32x4 rsrc, uint32_t wave_tile, int soff) const {
+        if constexpr (NI == 4) {
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\t"
+                         "buffer_load_dwordx4 %1, %5, %6 offen lds\n\t"
+                         "buffer_load_dwordx4 %2, %5, %6 offen offset:1024 lds\n\t"
+                         "buffer_load_dwordx4 %3, %5, %6 offen offset:2048 lds\n\t"
+                         "buffer_load_dwordx4 %4, %5, %6 offen offset:3072 lds"
+                         :: "s"(wave_tile), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(rsrc), "s"(soff)
+                         : "memory", "m0");
+        } else {
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\t"
+                         "buffer_load_dwordx4 %1, %3, %4 offen lds\n\t"
+                         "buffer_load_dwordx4 %2, %3, %4 offen offset:1024 lds"
+                         :: "s"(wave_tile), "v"(voff[0]), "v"(voff[1]), "s"(rsrc), "s"(soff) : "memory", "m0");
+        }
     }
 };
 
