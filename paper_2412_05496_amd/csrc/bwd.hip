@@ -42,6 +42,8 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
         return rc;
     if ((rc = check_extent(Q, dims->q_len, dims->D)) != FLEXATTN_OK) return rc;
     if ((rc = check_extent(dO, dims->q_len, dims->D)) != FLEXATTN_OK) return rc;
+    if ((rc = check_extent(K, dims->kv_len, dims->D)) != FLEXATTN_OK) return rc;
+    if ((rc = check_extent(V, dims->kv_len, dims->D)) != FLEXATTN_OK) return rc;
     static const flexattn_tensor kNoTensor = {nullptr, 0, 0, 0};
     if (!(stages & FLEXATTN_BWD_DQ)) dQ = &kNoTensor;
     if (!(stages & FLEXATTN_BWD_DKDV)) dK = dV = &kNoTensor;

@@ -86,12 +86,12 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const BwdArgs a) {
 
 // Issue order of the MFMAs of one dK/dV step (see bwd_dkdv_kernel).  MFMA ids: [0, N1) are S / dP
 // of the next step (alternating, k-slice id / 2); N1 + c * N3H + j are dV^T (j even) / dK^T (j odd)
-// of this step for the 16-row slice c and output block j / 2.  Chunk i < 8 carries score elements
-// 2i, 2i+1; slice 0 needs elements 0..7 (chunks 0..3) and is issued in chunks 4..7, slice 1 needs
-// all sixteen and forms the four tail chunks.
+// of this step for the 16-row slice c and output block j / 2.  Chunk i < 4 carries score elements
+// 4i .. 4i+3; slice 0 needs elements 0..7 (chunks 0, 1) and is issued in chunks 2, 3; slice 1 needs
+// all sixteen and forms the two tail chunks.
 template <int D>
 struct DkdvSchedule {
-    static constexpr int N1 = D / 8, N3H = D / 16, NM = N1 + 2 * N3H, NCHUNK = 12;
+    static constexpr int N1 = D / 8, N3H = D / 16, NM = N1 + 2 * N3H, NCHUNK = 6;
     int order[NM];
     int begin[NCHUNK + 1];
     static constexpr DkdvSchedule make() {
@@ -99,12 +99,12 @@ struct DkdvSchedule {
         int n = 0;
         for (int i = 0; i < NCHUNK; ++i) {
             s.begin[i] = n;
-            if (i < 8)
-                for (int m = i * N1 / 8; m < (i + 1) * N1 / 8; ++m) s.order[n++] = m;
-            if (i >= 4 && i < 8)
-                for (int m = (i - 4) * N3H / 4; m < (i - 3) * N3H / 4; ++m) s.order[n++] = N1 + m;
-            if (i >= 8)
-                for (int m = (i - 8) * N3H / 4; m < (i - 7) * N3H / 4; ++m) s.order[n++] = N1 + N3H + m;
+            if (i < 4)
+                for (int m = i * N1 / 4; m < (i + 1) * N1 / 4; ++m) s.order[n++] = m;
+            if (i >= 2 && i < 4)
+                for (int m = (i - 2) * N3H / 2; m < (i - 1) * N3H / 2; ++m) s.order[n++] = N1 + m;
+            if (i >= 4)
+                for (int m = (i - 4) * N3H / 2; m < (i - 3) * N3H / 2; ++m) s.order[n++] = N1 + N3H + m;
         }
         s.begin[NCHUNK] = n;
         return s;
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
     constexpr int TILE = TQ * D;                   // elements per LDS tile
     constexpr int NBUF = 4;
     constexpr int NKS = D / 16, NDB = D / 32;
-    using Loader = WaveTileLoader<D>;
+    using Loader = WaveTileLoader<D, 4>;
     constexpr int kLoads = 2 * Loader::NI + 1;     // buffer loads per wave and step
     constexpr int kWaitOlder = 0x0F70 | kLoads;    // s_waitcnt vmcnt(kLoads): all but the newest step
     static_assert(kLoads <= 15, "vmcnt immediate");
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
 
     const int sub = a.Bq / TQ;          // steps per BlockMask row block
     const Loader q_loader(a.q_ss, w, lane), do_loader(a.do_ss, w, lane);
-    const uint32_t wave_q = lds_addr(smem) + w * (Loader::NI * 1024);    // this wave's part of Q tile 0
+    const uint32_t ring = lds_addr(smem);
     const uint32_t wave_row = lds_addr(&s_row[0][w & 1][0]);
     const uint32_t q_bytes = (uint32_t)((a.q_len - 1) * a.q_ss + D) * 2u;
     const uint32_t do_bytes = (uint32_t)((a.q_len - 1) * a.do_ss + D) * 2u;
@@ -229,8 +229,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             const int q0 = blk_cur * a.Bq + ld_s * TQ;
             q0_of[SLOT] = q0;
             part_of[SLOT] = ld_pos >= n_full;
-            q_loader.start(q_rsrc, wave_q + SLOT * 2 * (TILE * 2), q0 * q_row_bytes);
-            do_loader.start(do_rsrc, wave_q + (SLOT * 2 + 1) * (TILE * 2), q0 * do_row_bytes);
+            q_loader.start(q_rsrc, ring + SLOT * 2 * (TILE * 2), q0 * q_row_bytes);
+            do_loader.start(do_rsrc, ring + (SLOT * 2 + 1) * (TILE * 2), q0 * do_row_bytes);
             dma_dword(row_rsrc, wave_row + SLOT * 2 * TQ * 4, lane * 4, q0 * 4);
             if (--ld_s < 0) {
                 ld_s = sub - 1;
@@ -298,29 +298,41 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             const int q_first = q0_of[SLOT] + 32 * qh;
 
             u32x4 pk[2], dsk[2];
-            auto element_pair = [&](int e) {
-                float pe[2], ds[2];
+            // four score elements at a time, stage by stage, so that no vector instruction has to
+            // wait for the one issued just before it
+            auto element_quad = [&](int c4) {
+                float sv[4], rcv[4], gr[4], pe[4], ds[4];
+                int dqk[4];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int r = 2 * e + i;
-                    float gr;
+                for (int i = 0; i < 4; ++i) {
+                    const int r = 4 * c4 + i;
+                    sv[i] = sacc[r];
+                    rcv[i] = rc_cur[r >> 2][r & 3];
                     // alibi / rel-bias need q - kv; the soft-cap and the plain score do not
-                    const int dqk = (ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel) ? q_first + crow(r, half) - kv_lane : 0;
-                    pe[i] = smod.p_with_grad(sacc[r], dqk, rc_cur[r >> 2][r & 3], gr);
-                    ds[i] = pe[i] * gr * dpacc[r];
+                    dqk[i] = (ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel) ? q_first + crow(r, half) - kv_lane : 0;
                 }
+                smod.p_with_grad4(sv, dqk, rcv, gr, pe);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ds[i] = pe[i] * gr[i];
+                pin4(ds);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ds[i] *= dpacc[4 * c4 + i];
                 if (partial) {
                     asm volatile("" ::: "memory");   // keep this a (scalar, rarely taken) branch
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        const MaskRow<MASK> mrow(a.p, b, hq, q_first + crow(2 * e + i, half));
+                    for (int i = 0; i < 4; ++i) {
+                        const MaskRow<MASK> mrow(a.p, b, hq, q_first + crow(4 * c4 + i, half));
                         const bool keep = mrow(kv_lane);
                         pe[i] = keep ? pe[i] : 0.0f;
                         ds[i] = keep ? ds[i] : 0.0f;
                     }
                 }
-                pk[e >> 2][e & 3] = pack_bf16(pe[0], pe[1]);
-                dsk[e >> 2][e & 3] = pack_bf16(ds[0], ds[1]);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int e = 2 * c4 + i;
+                    pk[e >> 2][e & 3] = pack_bf16(pe[2 * i], pe[2 * i + 1]);
+                    dsk[e >> 2][e & 3] = pack_bf16(ds[2 * i], ds[2 * i + 1]);
+                }
             };
             constexpr int N1 = 2 * NKS, N3H = 2 * NDB, NM = N1 + 2 * N3H;
             auto frag_load = [&](int m) {
@@ -355,7 +367,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
                     if (sq + PF < NM) fr[kSched.order[sq + PF]] = frag_load(kSched.order[sq + PF]);
                     mfma_op(kSched.order[sq], fr[kSched.order[sq]]);
                 }
-                if (i < 8) element_pair(i);
+                if (i < 4) element_quad(i);
                 if (i == kSched.NCHUNK - 1) read_rows(NEXT, 0, rc_cur);   // for the next step's elements
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -431,13 +443,12 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     const int g = rem % a.G;
     const int b = unit / a.Hkv, hkv = unit % a.Hkv, hq = hkv * a.G + g;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q_row = row * Bq + w * 32 + l32;
 
     const int64_t line = ((int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hq : 0)) * a.NR + row;
-    const int n_full = a.full_kv_num[line], n_part = a.kv_num[line];
-    const int32_t* full_idx = a.full_kv_idx + line * a.NC;
-    const int32_t* part_idx = a.kv_idx + line * a.NC;
+    const int n_full = ldc(a.full_kv_num + line), n_part = ldc(a.kv_num + line);
     const int sub = a.Bk / 64;
     const int T = (n_full + n_part) * sub;
 
@@ -459,20 +470,17 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     }
     const int64_t rowi = ((int64_t)b * a.Hq + hq) * a.q_len + q_row;
     const float lse2 = a.lse2[rowi], neg_delta = a.delta[rowi];
-    const bf16* k_base = a.K + b * a.k_sb + hkv * a.k_sh;
-    const bf16* v_base = a.V + b * a.v_sb + hkv * a.v_sh;
+    const i32x4 k_rsrc = make_rsrc(a.K + b * a.k_sb + hkv * a.k_sh, (uint32_t)((a.kv_len - 1) * a.k_ss + D) * 2u);
+    const i32x4 v_rsrc = make_rsrc(a.V + b * a.v_sb + hkv * a.v_sh, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
+    const int k_row_bytes = (int)a.k_ss * 2, v_row_bytes = (int)a.v_ss * 2;
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
     const MaskRow<MASK> mrow(a.p, b, hq, q_row);
 
-    auto tile_kv0 = [&](int t) {
-        const int pos = t / sub, s = t - pos * sub;
-        const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
-        return blk * a.Bk + s * 64;
-    };
-    const TileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
-    auto load_tiles = [&](int t, int kv0) {
-        k_loader.start(smem + (t & 1) * TILE, k_base + (int64_t)kv0 * a.k_ss);
-        v_loader.start(smem + (2 + (t & 1)) * TILE, v_base + (int64_t)kv0 * a.v_ss);
+    TileWalk walk(a.full_kv_idx + line * a.NC, a.kv_idx + line * a.NC, n_full, n_part, sub, a.Bk);
+    const WaveTileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
+    auto load_tiles = [&](int buf, int kv0) {
+        k_loader.start(k_rsrc, lds_addr(smem) + buf * (TILE * 2), kv0 * k_row_bytes);
+        v_loader.start(v_rsrc, lds_addr(smem) + (2 + buf) * (TILE * 2), kv0 * v_row_bytes);
     };
     const RowReader<D> row_reader(l32, half, lds_addr(smem));
     const TrReader<D> tr_reader(lane, lds_addr(smem));
@@ -484,7 +492,8 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[db][r] = 0.0f;
 
-    int kv0 = tile_kv0(0);
+    bool part_next = false;
+    int kv0 = walk.next(part_next);
     load_tiles(0, kv0);
     wait_vmem();
     __syncthreads();
@@ -493,11 +502,11 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     auto step = [&](int t, auto buf_tag) {
         constexpr int BUF = decltype(buf_tag)::value;
         const int kv0_cur = kv0;
+        const bool partial = part_next;
         if (t + 1 < T) {
-            kv0 = tile_kv0(t + 1);
-            load_tiles(t + 1, kv0);          // buffer BUF ^ 1 was last read in step t-1
+            kv0 = walk.next(part_next);
+            load_tiles(BUF ^ 1, kv0);        // buffer BUF ^ 1 was last read in step t-1
         }
-        const bool partial = (t / sub) >= n_full;
         constexpr uint32_t kt = BUF * (TILE * 2), vt = (2 + BUF) * (TILE * 2);
 
 #pragma unroll
@@ -507,7 +516,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 sacc[r] = 0.0f;
-                dpacc[r] = 0.0f;
+                dpacc[r] = neg_delta;        // dP - delta comes out of the accumulation
             }
 #pragma unroll
             for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(row_reader.read(kt, kvb * 32, ks), qf[ks], sacc);
@@ -518,7 +527,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
                 const int kv = kv0_cur + kvb * 32 + crow(r, half);
                 float gr;
                 const float pe = smod.p_with_grad(sacc[r], q_row - kv, rc, gr);
-                dpacc[r] = pe * (dpacc[r] + neg_delta) * gr;
+                dpacc[r] = pe * gr * dpacc[r];
             }
             if (partial) {
                 asm volatile("" ::: "memory");   // keep this a branch

@@ -104,6 +104,12 @@ struct MaskRow {
 // so that exp(score') = exp2(apply(...)).  Order: ALiBi, relative bias, soft-cap.
 // dscore(x) is d score_mod / d s given x = apply(...), used by the backward pass.
 // ---------------------------------------------------------------------------------------
+// Compiler-only fence on four values: everything that produces them is ordered before everything
+// that uses them afterwards (no instruction is emitted).
+__device__ __forceinline__ void pin4(float (&v)[4]) {
+    asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
+}
+
 template <uint32_t SCORE>
 struct ScoreMod {
     static constexpr bool kAlibi = SCORE & FLEXATTN_SCORE_ALIBI;
@@ -184,6 +190,43 @@ struct ScoreMod {
     // Backward: P = exp(score' - LSE) from the raw dot product, with the row's constant folded in.
     // row_const() maps LSE * log2(e) (+inf for a row without visible keys) to that constant.
     __device__ __forceinline__ float row_const(float lse2) const { return kCap ? capl2 - lse2 : -lse2; }
+    // The same for four independent elements, written stage by stage (pin4 keeps the stages apart):
+    // a wave that is alone on its SIMD loses several cycles on every vector instruction that
+    // consumes the result of the one before it.
+    __device__ __forceinline__ void p_with_grad4(const float (&acc)[4], const int (&dq)[4], const float (&rc)[4],
+                                                 float (&g)[4], float (&p)[4]) const {
+        float x[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = pre(acc[i], dq[i]);
+        pin4(x);
+        if constexpr (kCap) {
+            float r[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = fast_exp2(x[i]);
+            pin4(x);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = 1.0f + x[i];
+            pin4(x);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = fast_rcp(x[i]);
+            pin4(r);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = __builtin_fmaf(-2.0f * capl2, r[i], rc[i]);
+            pin4(x);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) g[i] = __builtin_fmaf(-r[i], r[i], r[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[i] += rc[i];
+                g[i] = 1.0f;
+            }
+            pin4(x);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = fast_exp2(x[i]);
+        pin4(p);
+    }
     __device__ __forceinline__ float p_with_grad(float acc, int dq, float rc, float& g) const {
         if constexpr (kCap) {
             const float r = cap_r(acc, dq);

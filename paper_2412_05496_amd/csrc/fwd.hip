@@ -71,6 +71,7 @@ extern "C" int flexattn_forward(const flexattn_dims* dims, const flexattn_tensor
     int rc = check_problem(dims, bm);
     if (rc != FLEXATTN_OK) return rc;
     if ((rc = check_tensor(Q)) || (rc = check_tensor(K)) || (rc = check_tensor(V)) || (rc = check_tensor(O))) return rc;
+    if ((rc = check_extent(K, dims->kv_len, dims->D)) || (rc = check_extent(V, dims->kv_len, dims->D))) return rc;
     if (!LSE || !(scale > 0.0f)) return FLEXATTN_ERR_INVALID_ARG;
     if ((rc = check_mod_params(mask_id, score_id, params)) != FLEXATTN_OK) return rc;
     const int vi = find_variant(mask_id, score_id);

@@ -65,13 +65,12 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     const int g = rem % a.G;
     const int b = unit / a.Hkv, hkv = unit % a.Hkv, hq = hkv * a.G + g;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q_row = row * Bq + w * 32 + l32;
 
     const int64_t line = ((int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hq : 0)) * a.NR + row;
-    const int n_full = a.full_num[line], n_part = a.kv_num[line];
-    const int32_t* full_idx = a.full_idx + line * a.NC;
-    const int32_t* part_idx = a.kv_idx + line * a.NC;
+    const int n_full = ldc(a.full_num + line), n_part = ldc(a.kv_num + line);
     const int T = (n_full + n_part) * a.sub;
 
     bf16* o_ptr = a.O + b * a.o_sb + hq * a.o_sh + (int64_t)q_row * a.o_ss;
@@ -89,24 +88,25 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *(const bf16x8*)(qp + ks * 16);
     }
-    const bf16* k_base = a.K + b * a.k_sb + hkv * a.k_sh;
-    const bf16* v_base = a.V + b * a.v_sb + hkv * a.v_sh;
+    const i32x4 k_rsrc = make_rsrc(a.K + b * a.k_sb + hkv * a.k_sh, (uint32_t)((a.kv_len - 1) * a.k_ss + D) * 2u);
+    const i32x4 v_rsrc = make_rsrc(a.V + b * a.v_sb + hkv * a.v_sh, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
+    const int k_row_bytes = (int)a.k_ss * 2, v_row_bytes = (int)a.v_ss * 2;
 
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
     const MaskRow<MASK> mrow(a.p, b, hq, q_row);
     const float neg2c = -2.0f * smod.capl2;
 
-    auto tile_kv0 = [&](int t) {
-        const int pos = t / a.sub, s = t - pos * a.sub;
-        const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
-        return blk * a.Bk + s * kTileKV;
-    };
-    const TileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
-    auto load_k = [&](int t) { k_loader.start(smem + (t & 1) * TILE, k_base + (int64_t)tile_kv0(t) * a.k_ss); };
-    auto load_v = [&](int t) { v_loader.start(smem + (2 + (t & 1)) * TILE, v_base + (int64_t)tile_kv0(t) * a.v_ss); };
+    // first key and PARTIAL flag of tiles t, t+1, t+2 (the walk is always two tiles ahead)
+    TileWalk walk(a.full_idx + line * a.NC, a.kv_idx + line * a.NC, n_full, n_part, a.sub, a.Bk);
+    int kv_t = 0, kv_t1 = 0, kv_t2 = 0;
+    bool part_t = false, part_t1 = false, part_t2 = false;
+    const uint32_t smem_bytes = lds_addr(smem);
+    const WaveTileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
+    // buf = tile index & 1
+    auto load_k = [&](int buf, int kv0) { k_loader.start(k_rsrc, smem_bytes + buf * (TILE * 2), kv0 * k_row_bytes); };
+    auto load_v = [&](int buf, int kv0) { v_loader.start(v_rsrc, smem_bytes + (2 + buf) * (TILE * 2), kv0 * v_row_bytes); };
     const RowReader<D> k_reader(l32, half);
     const TrReader<D> v_reader(lane);
-    const uint32_t smem_bytes = lds_addr(smem);
 
     // S^T = K Q^T for the two 32-key blocks of the K tile in buffer BUF (compile-time)
     auto qk = [&](auto buf_tag, f32x16 (&s)[2]) {
@@ -195,9 +195,13 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     };
 
     // ---- prologue: K(0), V(0), K(1) in flight; S^T(0)
-    load_k(0);
-    load_v(0);
-    if (T > 1) load_k(1);
+    kv_t = walk.next(part_t);
+    load_k(0, kv_t);
+    load_v(0, kv_t);
+    if (T > 1) {
+        kv_t1 = walk.next(part_t1);
+        load_k(1, kv_t1);
+    }
     wait_vmem();
     __syncthreads();
     f32x16 s_cur[2], s_next[2];
@@ -212,10 +216,13 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
         // nobody still reads K(t) [buffer BUF] or V(t-1) [buffer BUF ^ 1], which are refilled next.
         wait_vmem();
         __syncthreads();
-        if (t + 2 < T) load_k(t + 2);
-        if constexpr (HAS_NEXT) load_v(t + 1);
-        const int kv0 = tile_kv0(t);
-        const bool partial = (t / a.sub) >= n_full;
+        if (t + 2 < T) {
+            kv_t2 = walk.next(part_t2);
+            load_k(BUF, kv_t2);
+        }
+        if constexpr (HAS_NEXT) load_v(BUF ^ 1, kv_t1);
+        const int kv0 = kv_t;
+        const bool partial = part_t;
         bf16x8 pf[2];
         if constexpr (HAS_NEXT) qk(std::integral_constant<int, BUF ^ 1>{}, s_next);
         softmax(s_cur[0], kv0, partial, pf);
@@ -226,6 +233,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
 #pragma unroll
             for (int kvb = 0; kvb < 2; ++kvb) s_cur[kvb] = s_next[kvb];
         }
+        kv_t = kv_t1, part_t = part_t1;
+        kv_t1 = kv_t2, part_t1 = part_t2;
     };
     {
         const std::integral_constant<int, 0> b0;

@@ -71,55 +71,71 @@ struct TileLoader {
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ i32x4 make_rsrc(const void* p, uint32_t bytes) {
     const uint64_t addr = (uint64_t)p;
-    return i32x4{(int)(uint32_t)addr, (int)((uint32_t)(addr >> 32) & 0xffffu), (int)bytes, 0x00020000};
+    // (readfirstlane: the descriptor must sit in scalar registers whatever the compiler believes
+    // about the uniformity of p)
+    return i32x4{__builtin_amdgcn_readfirstlane((int)(uint32_t)addr),
+                 __builtin_amdgcn_readfirstlane((int)((uint32_t)(addr >> 32) & 0xffffu)),
+                 __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
 }
 
 // LDS-DMA loads are issued from inline assembly on purpose.  When the compiler sees such a load it
 // makes every later LDS read that it cannot prove disjoint wait for vmcnt(0), which serialises the
 // prefetch with the compute it is meant to overlap; completion is tracked by hand instead
 // (s_waitcnt vmcnt + barrier before a buffer is read).  s_nop 4 covers the wait states between a
-// write of M0 (or of a scalar operand by a vector instruction) and the loads that use it.
+// write of M0 (or of a scalar operand by a vector instruction) and the loads that use it.  M0 is
+// written without telling the compiler (it does not accept M0 as a clobber): the kernels that
+// use these helpers contain nothing else that needs M0.
 //
 // dma_dword: 64 lanes x 4 bytes to `lds` .. +256.
 __device__ __forceinline__ void dma_dword(i32x4 rsrc, uint32_t lds, int voff, int soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
 
-// The tile copy with buffer loads (buffer_load_dwordx4 ... lds), for a workgroup of 4 waves: the
-// row of the tile is selected by a scalar byte offset, so starting a tile costs one M0 write and
-// NI loads and no vector arithmetic.  Wave w fills the contiguous LDS bytes
-// [w * 1024 * NI, (w + 1) * 1024 * NI) of the tile; the instruction's immediate offset moves the LDS
-// destination by 1 KiB per load and, because it is added to the memory address as well, is taken
-// out of the per-lane offsets again (they stay non-negative as long as the row stride is >= D).
-template <int D>
+// dma_x4 / dma_x2: four (two) 1 KiB loads to `lds` + 0, 1024, 2048, 3072.  The immediate offset
+// moves the LDS destination and, because it is added to the memory address as well, has been
+// taken out of the per-lane offsets v0..v3 by the caller.
+__device__ __forceinline__ void dma_x4(i32x4 rsrc, uint32_t lds, int v0, int v1, int v2, int v3, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\t"
+                 "buffer_load_dwordx4 %1, %5, %6 offen lds\n\t"
+                 "buffer_load_dwordx4 %2, %5, %6 offen offset:1024 lds\n\t"
+                 "buffer_load_dwordx4 %3, %5, %6 offen offset:2048 lds\n\t"
+                 "buffer_load_dwordx4 %4, %5, %6 offen offset:3072 lds"
+                 :: "s"(lds), "v"(v0), "v"(v1), "v"(v2), "v"(v3), "s"(rsrc), "s"(soff) : "memory");
+}
+__device__ __forceinline__ void dma_x2(i32x4 rsrc, uint32_t lds, int v0, int v1, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\t"
+                 "buffer_load_dwordx4 %1, %3, %4 offen lds\n\t"
+                 "buffer_load_dwordx4 %2, %3, %4 offen offset:1024 lds"
+                 :: "s"(lds), "v"(v0), "v"(v1), "s"(rsrc), "s"(soff) : "memory");
+}
+
+// The tile copy with buffer loads, for a workgroup of NW waves: the row of the tile is selected by
+// a scalar byte offset, so starting a tile costs an M0 write per four loads and no vector
+// arithmetic.  Wave w fills the contiguous LDS bytes [w * 1024 * NI, (w + 1) * 1024 * NI) of the
+// tile.  The per-lane offsets stay non-negative as long as the row stride is >= D.
+// Completion: s_waitcnt vmcnt by every wave, then a barrier.
+template <int D, int NW>
 struct WaveTileLoader {
-    static constexpr int DC = D / 8, RPI = 64 / DC, NI = D / 32;
-    static_assert(NI == 2 || NI == 4, "D is 64 or 128");
+    static constexpr int DC = D / 8, RPI = 64 / DC, NI = DC / NW;   // NI loads per wave
+    static_assert(NI == 2 || NI == 4 || NI == 8, "D is 64 or 128, 2 or 4 waves");
     int32_t voff[NI];                           // per-lane byte offsets
-    __device__ __forceinline__ WaveTileLoader(int64_t gs, int wave, int lane) {
+    uint32_t wave_off;                          // of this wave's part inside a tile
+    __device__ __forceinline__ WaveTileLoader(int64_t gs, int wave, int lane) : wave_off(wave * NI * 1024) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int row = (wave * NI + i) * RPI + lane / DC;
-            voff[i] = (int32_t)(row * gs * 2) + (((lane % DC) ^ swz<D>(row)) * 16) - i * 1024;
+            voff[i] = (int32_t)(row * gs * 2) + (((lane % DC) ^ swz<D>(row)) * 16) - (i & 3) * 1024;
         }
     }
-    // `wave_tile`: LDS byte address of this wave's part of the tile (wave-uniform);
+    // `tile`: LDS byte address of the tile (wave-uniform);
     // `soff`: byte offset of the tile's first row inside the resource (wave-uniform)
-    __device__ __forceinline__ void start(i32x4 rsrc, uint32_t wave_tile, int soff) const {
-        if constexpr (NI == 4) {
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\t"
-                         "buffer_load_dwordx4 %1, %5, %6 offen lds\n\t"
-                         "buffer_load_dwordx4 %2, %5, %6 offen offset:1024 lds\n\t"
-                         "buffer_load_dwordx4 %3, %5, %6 offen offset:2048 lds\n\t"
-                         "buffer_load_dwordx4 %4, %5, %6 offen offset:3072 lds"
-                         :: "s"(wave_tile), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(rsrc), "s"(soff)
-                         : "memory", "m0");
+    __device__ __forceinline__ void start(i32x4 rsrc, uint32_t tile, int soff) const {
+        if constexpr (NI == 2) {
+            dma_x2(rsrc, tile + wave_off, voff[0], voff[1], soff);
         } else {
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\t"
-                         "buffer_load_dwordx4 %1, %3, %4 offen lds\n\t"
-                         "buffer_load_dwordx4 %2, %3, %4 offen offset:1024 lds"
-                         :: "s"(wave_tile), "v"(voff[0]), "v"(voff[1]), "s"(rsrc), "s"(soff) : "memory", "m0");
+            dma_x4(rsrc, tile + wave_off, voff[0], voff[1], voff[2], voff[3], soff);
+            if constexpr (NI == 8) dma_x4(rsrc, tile + wave_off + 4096, voff[4], voff[5], voff[6], voff[7], soff);
         }
     }
 };
@@ -170,6 +186,37 @@ struct TrReader {
         const u32x2 hi = lds_read_tr4(tile_bytes + off[cb][1] + 2u * r0 * D);
         u32x4 f = {lo[0], lo[1], hi[0], hi[1]};
         return __builtin_bit_cast(bf16x8, f);
+    }
+};
+
+// Walk over the 64-wide tiles of the blocks a BlockMask lists for one row (or column) of blocks:
+// FULL blocks first, then PARTIAL ones, each block cut into `sub` tiles.  The block index of the
+// following block is fetched (scalar cache) when the walk enters a block, i.e. ahead of its use.
+struct TileWalk {
+    const int32_t* full_idx;
+    const int32_t* part_idx;
+    int n_full, n_blocks, sub, block_len;
+    int pos, s, blk;
+    __device__ __forceinline__ int block_at(int p) const {
+        return p < n_full ? ldc(full_idx + p) : ldc(part_idx + (p - n_full));
+    }
+    __device__ __forceinline__ TileWalk(const int32_t* full_idx_, const int32_t* part_idx_, int n_full_, int n_part,
+                                        int sub_, int block_len_)
+        : full_idx(full_idx_), part_idx(part_idx_), n_full(n_full_), n_blocks(n_full_ + n_part), sub(sub_),
+          block_len(block_len_), pos(0), s(0) {
+        blk = n_blocks > 0 ? block_at(0) : 0;
+    }
+    // first row (column) of the next tile, and whether its block is PARTIAL; must not be called
+    // more than n_blocks * sub times
+    __device__ __forceinline__ int next(bool& partial) {
+        const int x0 = blk * block_len + s * 64;
+        partial = pos >= n_full;
+        if (++s == sub) {
+            s = 0;
+            ++pos;
+            blk = pos < n_blocks ? block_at(pos) : 0;
+        }
+        return x0;
     }
 };
 
