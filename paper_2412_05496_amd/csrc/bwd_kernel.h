@@ -139,8 +139,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
     // ring of NBUF x (Q tile, dO tile); reused for the final reduction
     __shared__ __attribute__((aligned(1024))) bf16 smem[NBUF * 2 * TILE];
     __shared__ __attribute__((aligned(256))) float s_row[NBUF][2][TQ];   // [buffer][rc | -delta][row]
+    constexpr int kListMax = 4096;
+    __shared__ int s_steps[kListMax + 4];          // the walk of the current head, see below
     static_assert(sizeof(bf16) * NBUF * 2 * TILE >= sizeof(float) * 4 * D * 32, "reduction buffer must fit");
-
     // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
     const int units = a.B * a.Hkv;
     const int tiles = a.kv_len / 64;
@@ -204,8 +205,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
         const int n_full = a.full_q_num[line], n_part = a.q_num[line];
         const int32_t* full_idx = a.full_q_idx + line * a.NR;
         const int32_t* part_idx = a.q_idx + line * a.NR;
-        const int H = (n_full + n_part) * sub;      // steps
-        if (H == 0) continue;
+        const int H_all = (n_full + n_part) * sub;  // steps
+        if (H_all == 0) continue;
         const i32x4 q_rsrc = make_rsrc(a.Q + b * a.q_sb + hq * a.q_sh, q_bytes);
         const i32x4 do_rsrc = make_rsrc(a.dO + b * a.do_sb + hq * a.do_sh, do_bytes);
         // waves 0, 2 fetch the rc row, waves 1, 3 the -delta row (the duplicates write the same values)
@@ -213,31 +214,51 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             make_rsrc(((w & 1) ? a.delta : a.lse2) + ((int64_t)b * a.Hq + hq) * a.q_len, (uint32_t)a.q_len * 4u);
         const ScoreMod<SCORE> smod(a.p, hq, a.scale);
 
-        // The merged list (FULL blocks, then PARTIAL ones) is walked from its END, one block index
-        // fetched ahead of its use.  ld_* describe the step whose loads are issued next.
-        auto block_at = [&](int pos) { return pos < n_full ? ldc(full_idx + pos) : ldc(part_idx + (pos - n_full)); };
-        int ld_pos = n_full + n_part - 1, ld_s = sub - 1;
-        int blk_cur = block_at(ld_pos);
-        int blk_nxt = ld_pos > 0 ? block_at(ld_pos - 1) : 0;
+        // The merged list (FULL blocks, then PARTIAL ones) is walked from its END (see above).  The
+        // walk is laid out in LDS first, kListMax steps at a time -- one entry per step: first query
+        // row | 1 if the block is PARTIAL -- so that the main loop finds the next row offset with one
+        // LDS read issued a step ahead instead of a chain of dependent scalar loads.
+      for (int seg0 = 0; seg0 < H_all; seg0 += kListMax) {
+        const int H = min(kListMax, H_all - seg0);
+        for (int i = tid; i < H; i += 256) {
+            const int u = H_all - 1 - (seg0 + i), pos = u / sub, sidx = u - pos * sub;
+            const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
+            s_steps[i] = (blk * a.Bq + sidx * TQ) | (pos >= n_full ? 1 : 0);
+            // loads are issued for three steps past the end as well (into free ring slots, never
+            // read): they repeat the last step's rows
+            if (i == H - 1) s_steps[H] = s_steps[H + 1] = s_steps[H + 2] = s_steps[H + 3] = s_steps[i];
+        }
+        __syncthreads();
+        int ld_v = 0;                               // step whose loads are issued next
+        int e_next = s_steps[0];
+        int ld_q0 = 0;                              // its first row, set by load_begin
         int q0_of[NBUF];                            // first query row of the step in each ring slot,
         bool part_of[NBUF];                         // and whether its block is PARTIAL
 
-        // Starts the loads of the next step into ring slot SLOT: exactly kLoads instructions per wave
-        // (the wait counts rely on it).
-        auto load_step = [&](auto slot_tag) {
+        // The loads of one step into ring slot SLOT are exactly kLoads instructions per wave (the
+        // wait counts rely on it), issued as load_begin, load_piece<0 .. kLoads-1>.
+        auto load_begin = [&](auto slot_tag) {
             constexpr int SLOT = decltype(slot_tag)::value;
-            const int q0 = blk_cur * a.Bq + ld_s * TQ;
-            q0_of[SLOT] = q0;
-            part_of[SLOT] = ld_pos >= n_full;
-            q_loader.start(q_rsrc, ring + SLOT * 2 * (TILE * 2), q0 * q_row_bytes);
-            do_loader.start(do_rsrc, ring + (SLOT * 2 + 1) * (TILE * 2), q0 * do_row_bytes);
-            dma_dword(row_rsrc, wave_row + SLOT * 2 * TQ * 4, lane * 4, q0 * 4);
-            if (--ld_s < 0) {
-                ld_s = sub - 1;
-                --ld_pos;
-                blk_cur = blk_nxt;
-                blk_nxt = ld_pos > 0 ? block_at(ld_pos - 1) : 0;
-            }
+            const int e = __builtin_amdgcn_readfirstlane(e_next);
+            ld_q0 = e & ~1;
+            q0_of[SLOT] = ld_q0;
+            part_of[SLOT] = e & 1;
+            e_next = s_steps[++ld_v];
+        };
+        auto load_piece = [&](auto slot_tag, auto piece_tag) {
+            constexpr int SLOT = decltype(slot_tag)::value, P = decltype(piece_tag)::value;
+            if constexpr (P < Loader::NI)
+                q_loader.template start_one<P>(q_rsrc, ring + SLOT * 2 * (TILE * 2), ld_q0 * q_row_bytes);
+            else if constexpr (P < 2 * Loader::NI)
+                do_loader.template start_one<P - Loader::NI>(do_rsrc, ring + (SLOT * 2 + 1) * (TILE * 2), ld_q0 * do_row_bytes);
+            else
+                dma_dword(row_rsrc, wave_row + SLOT * 2 * TQ * 4, lane * 4, ld_q0 * 4);
+        };
+        auto load_step = [&](auto slot_tag) {       // all at once (prologue)
+            load_begin(slot_tag);
+            q_loader.start(q_rsrc, ring + decltype(slot_tag)::value * 2 * (TILE * 2), ld_q0 * q_row_bytes);
+            do_loader.start(do_rsrc, ring + (decltype(slot_tag)::value * 2 + 1) * (TILE * 2), ld_q0 * do_row_bytes);
+            load_piece(slot_tag, std::integral_constant<int, kLoads - 1>{});
         };
         // this lane's 16 row scalars of a step: rows 8 rg + 4 half + {0..3} of the wave's 32
         auto read_rows = [&](int slot, int which, f32x4 (&out)[4]) {
@@ -258,10 +279,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
 
         // ---- prologue: steps 0 and 1 in flight, S and dP of step 0
         load_step(std::integral_constant<int, 0>{});
-        if (H > 1) load_step(std::integral_constant<int, 1>{});
-        if (H > 1) __builtin_amdgcn_s_waitcnt(kWaitOlder); else wait_vmem();      // step 0 has landed
+        load_step(std::integral_constant<int, 1>{});
+        __builtin_amdgcn_s_waitcnt(kWaitOlder);     // step 0 has landed
         __syncthreads();
-        if (H > 2) load_step(std::integral_constant<int, 2>{});
+        load_step(std::integral_constant<int, 2>{});
         {
             f32x4 nd[4];
             read_rows(0, 1, nd);
@@ -289,11 +310,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
 
             // Step v+1 must have landed (it is read below), step v+2 may still be in flight; after the
             // barrier nobody reads step v-1 any more and its slot takes step v+3.
-            if (v + 2 < H) __builtin_amdgcn_s_waitcnt(kWaitOlder); else wait_vmem();
+            __builtin_amdgcn_s_waitcnt(kWaitOlder);
             __syncthreads();
             f32x4 nd[4];
             read_rows(NEXT, 1, nd);                  // -delta of step v+1: dP starts from it
-            if (v + 3 < H) load_step(std::integral_constant<int, (SLOT + 3) & (NBUF - 1)>{});
+            constexpr std::integral_constant<int, (SLOT + 3) & (NBUF - 1)> ld_slot{};
+            load_begin(ld_slot);
             const bool partial = part_of[SLOT];
             const int q_first = q0_of[SLOT] + 32 * qh;
 
@@ -360,8 +382,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             bf16x8 fr[NM];
 #pragma unroll
             for (int sq = 0; sq < PF; ++sq) fr[kSched.order[sq]] = frag_load(kSched.order[sq]);
-#pragma unroll
-            for (int i = 0; i < kSched.NCHUNK; ++i) {
+            static_for<0, kSched.NCHUNK>([&](auto chunk_tag) {
+                constexpr int i = decltype(chunk_tag)::value;
+                // this chunk's share of the loads of step v+3
+                static_for<i * kLoads / kSched.NCHUNK, (i + 1) * kLoads / kSched.NCHUNK>(
+                    [&](auto piece_tag) { load_piece(ld_slot, piece_tag); });
 #pragma unroll
                 for (int sq = kSched.begin[i]; sq < kSched.begin[i + 1]; ++sq) {
                     if (sq + PF < NM) fr[kSched.order[sq + PF]] = frag_load(kSched.order[sq + PF]);
@@ -370,7 +395,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
                 if (i < 4) element_quad(i);
                 if (i == kSched.NCHUNK - 1) read_rows(NEXT, 0, rc_cur);   // for the next step's elements
                 __builtin_amdgcn_sched_barrier(0);
-            }
+            });
         };
 
         int v = 0;
@@ -384,7 +409,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
         if (v + 1 < H) step(v + 1, std::integral_constant<int, 1>{});
         if (v + 2 < H) step(v + 2, std::integral_constant<int, 2>{});
         wait_vmem();
-        __syncthreads();                // before the next head (or the reduction) reuses the ring
+        __syncthreads();                // before the next segment, head or the reduction reuses the LDS
+      }
     }
 
     // ---- add the two query-halves through LDS and write dK, dV (bf16)

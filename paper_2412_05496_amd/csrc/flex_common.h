@@ -2,6 +2,8 @@
 // the mask_mod / score_mod functors (paper sections 3.1 and 3.2) and host-side status helpers.
 #pragma once
 
+#include <type_traits>
+
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -32,6 +34,15 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // Row of the 32x32 result tile held in register r by a lane of half `half` (= lane / 32).
 __device__ __forceinline__ constexpr int crow(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
+
+// f(integral_constant<int, B>), ..., f(integral_constant<int, E - 1>)
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
 
 // Load of read-only data at a wave-uniform address: constant address space, so the compiler may
 // use the scalar cache and keep the load off the vector memory counter.

@@ -110,6 +110,11 @@ __device__ __forceinline__ void dma_x2(i32x4 rsrc, uint32_t lds, int v0, int v1,
                  :: "s"(lds), "v"(v0), "v"(v1), "s"(rsrc), "s"(soff) : "memory");
 }
 
+__device__ __forceinline__ void dma_x1(i32x4 rsrc, uint32_t lds, int v0, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds), "v"(v0), "s"(rsrc), "s"(soff) : "memory");
+}
+
 // The tile copy with buffer loads, for a workgroup of NW waves: the row of the tile is selected by
 // a scalar byte offset, so starting a tile costs an M0 write per four loads and no vector
 // arithmetic.  Wave w fills the contiguous LDS bytes [w * 1024 * NI, (w + 1) * 1024 * NI) of the
@@ -137,6 +142,13 @@ struct WaveTileLoader {
             dma_x4(rsrc, tile + wave_off, voff[0], voff[1], voff[2], voff[3], soff);
             if constexpr (NI == 8) dma_x4(rsrc, tile + wave_off + 4096, voff[4], voff[5], voff[6], voff[7], soff);
         }
+    }
+    // One of the NI loads on its own (I compile-time), for callers that spread the loads of a tile
+    // over their compute instead of issuing them back to back: the vector memory path takes a
+    // 1 KiB load every ~16 cycles per CU and a wave that finds its queue full stalls.
+    template <int I>
+    __device__ __forceinline__ void start_one(i32x4 rsrc, uint32_t tile, int soff) const {
+        dma_x1(rsrc, tile + wave_off + I * 1024, voff[I] + (I & 3) * 1024, soff);
     }
 };
 
