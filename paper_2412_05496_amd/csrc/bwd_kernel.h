@@ -84,64 +84,34 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const BwdArgs a) {
     }
 }
 
-// Issue order of the MFMAs of one dK/dV step (see bwd_dkdv_kernel).  MFMA ids: [0, N1) are S / dP
-// of the next step (alternating, k-slice id / 2); N1 + c * N3H + j are dV^T (j even) / dK^T (j odd)
-// of this step for the 16-row slice c and output block j / 2.  Chunk i < 4 carries score elements
-// 4i .. 4i+3; slice 0 needs elements 0..7 (chunks 0, 1) and is issued in chunks 2, 3; slice 1 needs
-// all sixteen and forms the two tail chunks.
-template <int D>
-struct DkdvSchedule {
-    static constexpr int N1 = D / 8, N3H = D / 16, NM = N1 + 2 * N3H, NCHUNK = 6;
-    int order[NM];
-    int begin[NCHUNK + 1];
-    static constexpr DkdvSchedule make() {
-        DkdvSchedule s{};
-        int n = 0;
-        for (int i = 0; i < NCHUNK; ++i) {
-            s.begin[i] = n;
-            if (i < 4)
-                for (int m = i * N1 / 4; m < (i + 1) * N1 / 4; ++m) s.order[n++] = m;
-            if (i >= 2 && i < 4)
-                for (int m = (i - 2) * N3H / 2; m < (i - 1) * N3H / 2; ++m) s.order[n++] = N1 + m;
-            if (i >= 4)
-                for (int m = (i - 4) * N3H / 2; m < (i - 3) * N3H / 2; ++m) s.order[n++] = N1 + N3H + m;
-        }
-        s.begin[NCHUNK] = n;
-        return s;
-    }
-};
-
 // ------------------------------------------------------------------------------------------
-// dK, dV.  256 threads = 4 waves, one workgroup per 64 keys, one wave per SIMD (the accumulators
-// need the whole register file).  The listed q-blocks are walked in steps of 64 query rows; wave w
-// owns keys 32 * (w & 1) .. +32 and rows 32 * (w >> 1) .. +32 of every step, i.e. one 32 x 32
-// score block per step, and the two waves that share keys add their accumulators through LDS at
-// the end.
-//
-// A single wave per SIMD pays for every instruction it issues and for every dependent pair of
-// vector instructions, so the step is kept short and is written as an explicit software pipeline:
-// chunks of (MFMAs, the LDS operand reads for a later chunk, the exp / dS arithmetic of two score
-// elements, interleaved) separated by scheduling barriers.  In step v the matrix pipe runs S and
-// dP of step v+1 and dV^T, dK^T of step v while the vector pipe turns S, dP of step v into P and
-// dS.  dP accumulates on top of -delta, so dP - delta costs nothing.  Q / dO tiles and the
-// per-row scalars sit in a ring of four LDS buffers filled by buffer loads issued three steps
-// ahead (scalar row offset, constant per-lane offsets); one barrier per step.
+// dK, dV.  256 threads = 4 waves, one workgroup per 64 keys of one (b, hkv), two workgroups per CU
+// (two waves per SIMD, from different workgroups, so that one wave's exp / dS arithmetic runs
+// beside the other's MFMAs).  The listed q-blocks are walked in steps of 64 query rows.  Wave
+// w = (kb, x), kb = w & 1, x = w >> 1:
+//   scores     S and dP - delta of the 32 x 32 block (rows 32 x .. +32 of the step, keys 32 kb .. +32),
+//              turned into P and dS (bf16, B-operand layout);
+//   exchange   the x = 0 wave hands its dS to the x = 1 wave of the same keys through LDS and gets
+//              that wave's P;
+//   outputs    the x = 0 wave accumulates dV^T += dO^T P over all 64 rows (its own P, then its
+//              partner's), the x = 1 wave dK^T += Q^T dS.  Each output row belongs to one wave: no
+//              reduction at the end, and 64 accumulator registers per lane instead of 128, which
+//              is what lets two workgroups share a CU.
+// Q / dO tiles and the per-row scalars are double buffered in LDS; the loads of step v+1 are
+// issued at the top of step v.  Two barriers per step: after the exchange writes, and at the end
+// (exchange buffer and ring slot free again, next tiles landed).
 template <int D, uint32_t MASK, uint32_t SCORE>
-__global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
+__global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
     constexpr int TQ = 64;                         // query rows per step
     constexpr int TILE = TQ * D;                   // elements per LDS tile
-    constexpr int NBUF = 4;
     constexpr int NKS = D / 16, NDB = D / 32;
     using Loader = WaveTileLoader<D, 4>;
-    constexpr int kLoads = 2 * Loader::NI + 1;     // buffer loads per wave and step
-    constexpr int kWaitOlder = 0x0F70 | kLoads;    // s_waitcnt vmcnt(kLoads): all but the newest step
-    static_assert(kLoads <= 15, "vmcnt immediate");
-    // ring of NBUF x (Q tile, dO tile); reused for the final reduction
-    __shared__ __attribute__((aligned(1024))) bf16 smem[NBUF * 2 * TILE];
-    __shared__ __attribute__((aligned(256))) float s_row[NBUF][2][TQ];   // [buffer][rc | -delta][row]
-    constexpr int kListMax = 4096;
-    __shared__ int s_steps[kListMax + 4];          // the walk of the current head, see below
-    static_assert(sizeof(bf16) * NBUF * 2 * TILE >= sizeof(float) * 4 * D * 32, "reduction buffer must fit");
+    __shared__ __attribute__((aligned(1024))) bf16 smem[2 * 2 * TILE];        // 2 x (Q tile, dO tile)
+    __shared__ __attribute__((aligned(1024))) u32x4 s_xchg[4][2][64];         // [wave][16-row slice][lane]
+    __shared__ __attribute__((aligned(256))) float s_row[2][2][TQ];           // [slot][rc | -delta][row]
+    constexpr int kListMax = 1024;
+    __shared__ int s_steps[kListMax + 2];          // the walk of the current head, see below
+
     // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
     const int units = a.B * a.Hkv;
     const int tiles = a.kv_len / 64;
@@ -155,7 +125,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kb = w & 1, qh = w >> 1;
+    const int kb = w & 1, x = w >> 1;
     const int kv_lane = kv0 + 32 * kb + l32;
 
     // K, V fragments of this wave's 32 keys: B operands (column = key, k-slots = dims)
@@ -170,14 +140,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
         }
     }
 
-    f32x16 dk[NDB], dv[NDB];
+    f32x16 acc[NDB];                    // x = 0: dV^T, x = 1: dK^T (row = dim, column = key)
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            dk[db][r] = 0.0f;
-            dv[db][r] = 0.0f;
-        }
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
 
     const int sub = a.Bq / TQ;          // steps per BlockMask row block
     const Loader q_loader(a.q_ss, w, lane), do_loader(a.do_ss, w, lane);
@@ -186,18 +153,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
     const uint32_t q_bytes = (uint32_t)((a.q_len - 1) * a.q_ss + D) * 2u;
     const uint32_t do_bytes = (uint32_t)((a.q_len - 1) * a.do_ss + D) * 2u;
     const int q_row_bytes = (int)a.q_ss * 2, do_row_bytes = (int)a.do_ss * 2;
-    // per-lane LDS addresses of this wave's 32 rows inside buffer 0 (Q copy; dO is one tile further)
-    const uint32_t my_rows = lds_addr(smem) + qh * 32 * D * 2;
-    // (an LDS instruction's immediate offset reaches 64 KiB: one set of addresses per half of the ring)
-    const RowReader<D> row_reader_lo(l32, half, my_rows), row_reader_hi(l32, half, my_rows + 65536);
-    const TrReader<D> tr_reader_lo(lane, my_rows), tr_reader_hi(lane, my_rows + 65536);
-    auto read_row = [&](uint32_t tile_bytes, int row0, int ks) {
-        return tile_bytes < 65536 ? row_reader_lo.read(tile_bytes, row0, ks) : row_reader_hi.read(tile_bytes - 65536, row0, ks);
-    };
-    auto read_tr = [&](uint32_t tile_bytes, int r0, int cb) {
-        return tile_bytes < 65536 ? tr_reader_lo.read(tile_bytes, r0, cb) : tr_reader_hi.read(tile_bytes - 65536, r0, cb);
-    };
-    const uint32_t row_lds = lds_addr(&s_row[0][0][0]) + (32 * qh + 4 * half) * 4;
+    // scores: this wave's 32 rows of the Q tile (the dO tile is one tile further)
+    const RowReader<D> row_reader(l32, half, ring + x * 32 * D * 2);
+    // outputs: the tile this wave contracts with (x = 0: dO, x = 1: Q), its own rows first, then
+    // its partner's
+    const uint32_t out_tile = ring + (x ? 0 : TILE * 2);
+    const TrReader<D> tr_own(lane, out_tile + x * 32 * D * 2), tr_other(lane, out_tile + (1 - x) * 32 * D * 2);
+    const uint32_t row_lds = lds_addr(&s_row[0][0][0]) + (32 * x + 4 * half) * 4;
+    const uint32_t xchg_mine = lds_addr(&s_xchg[w][0][lane]), xchg_theirs = lds_addr(&s_xchg[w ^ 2][0][lane]);
 
     for (int g = 0; g < a.G; ++g) {
         const int hq = hkv * a.G + g;
@@ -214,239 +177,159 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_kernel(const BwdArgs a) {
             make_rsrc(((w & 1) ? a.delta : a.lse2) + ((int64_t)b * a.Hq + hq) * a.q_len, (uint32_t)a.q_len * 4u);
         const ScoreMod<SCORE> smod(a.p, hq, a.scale);
 
-        // The merged list (FULL blocks, then PARTIAL ones) is walked from its END (see above).  The
-        // walk is laid out in LDS first, kListMax steps at a time -- one entry per step: first query
-        // row | 1 if the block is PARTIAL -- so that the main loop finds the next row offset with one
-        // LDS read issued a step ahead instead of a chain of dependent scalar loads.
-      for (int seg0 = 0; seg0 < H_all; seg0 += kListMax) {
-        const int H = min(kListMax, H_all - seg0);
-        for (int i = tid; i < H; i += 256) {
-            const int u = H_all - 1 - (seg0 + i), pos = u / sub, sidx = u - pos * sub;
-            const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
-            s_steps[i] = (blk * a.Bq + sidx * TQ) | (pos >= n_full ? 1 : 0);
-            // loads are issued for three steps past the end as well (into free ring slots, never
-            // read): they repeat the last step's rows
-            if (i == H - 1) s_steps[H] = s_steps[H + 1] = s_steps[H + 2] = s_steps[H + 3] = s_steps[i];
-        }
-        __syncthreads();
-        int ld_v = 0;                               // step whose loads are issued next
-        int e_next = s_steps[0];
-        int ld_q0 = 0;                              // its first row, set by load_begin
-        int q0_of[NBUF];                            // first query row of the step in each ring slot,
-        bool part_of[NBUF];                         // and whether its block is PARTIAL
-
-        // The loads of one step into ring slot SLOT are exactly kLoads instructions per wave (the
-        // wait counts rely on it), issued as load_begin, load_piece<0 .. kLoads-1>.
-        auto load_begin = [&](auto slot_tag) {
-            constexpr int SLOT = decltype(slot_tag)::value;
-            const int e = __builtin_amdgcn_readfirstlane(e_next);
-            ld_q0 = e & ~1;
-            q0_of[SLOT] = ld_q0;
-            part_of[SLOT] = e & 1;
-            e_next = s_steps[++ld_v];
-        };
-        auto load_piece = [&](auto slot_tag, auto piece_tag) {
-            constexpr int SLOT = decltype(slot_tag)::value, P = decltype(piece_tag)::value;
-            if constexpr (P < Loader::NI)
-                q_loader.template start_one<P>(q_rsrc, ring + SLOT * 2 * (TILE * 2), ld_q0 * q_row_bytes);
-            else if constexpr (P < 2 * Loader::NI)
-                do_loader.template start_one<P - Loader::NI>(do_rsrc, ring + (SLOT * 2 + 1) * (TILE * 2), ld_q0 * do_row_bytes);
-            else
-                dma_dword(row_rsrc, wave_row + SLOT * 2 * TQ * 4, lane * 4, ld_q0 * 4);
-        };
-        auto load_step = [&](auto slot_tag) {       // all at once (prologue)
-            load_begin(slot_tag);
-            q_loader.start(q_rsrc, ring + decltype(slot_tag)::value * 2 * (TILE * 2), ld_q0 * q_row_bytes);
-            do_loader.start(do_rsrc, ring + (decltype(slot_tag)::value * 2 + 1) * (TILE * 2), ld_q0 * do_row_bytes);
-            load_piece(slot_tag, std::integral_constant<int, kLoads - 1>{});
-        };
-        // this lane's 16 row scalars of a step: rows 8 rg + 4 half + {0..3} of the wave's 32
-        auto read_rows = [&](int slot, int which, f32x4 (&out)[4]) {
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg)
-                out[rg] = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(
-                    row_lds + (uint32_t)((slot * 2 + which) * TQ + 8 * rg) * 4);
-        };
-        auto as_acc = [](const f32x4 (&v)[4]) {
-            f32x16 o;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[r] = v[r >> 2][r & 3];
-            return o;
-        };
-
-        f32x16 s_even, dp_even, s_odd, dp_odd;      // S, dP - delta of even / odd steps
-        f32x4 rc_cur[4];
-
-        // ---- prologue: steps 0 and 1 in flight, S and dP of step 0
-        load_step(std::integral_constant<int, 0>{});
-        load_step(std::integral_constant<int, 1>{});
-        __builtin_amdgcn_s_waitcnt(kWaitOlder);     // step 0 has landed
-        __syncthreads();
-        load_step(std::integral_constant<int, 2>{});
-        {
-            f32x4 nd[4];
-            read_rows(0, 1, nd);
-            dp_even = as_acc(nd);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s_even[r] = 0.0f;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                s_even = mfma32(read_row(0, 0, ks), kf[ks], s_even);
-                dp_even = mfma32(read_row(TILE * 2, 0, ks), vf[ks], dp_even);
+        // The merged list (FULL blocks, then PARTIAL ones) is walked from its END: every workgroup of
+        // a head then spends most of its time descending from the last row block, so the workgroups
+        // that run side by side on an XCD ask its L2 for the same Q / dO tiles at about the same
+        // time.  The walk is laid out in LDS first, kListMax steps at a time -- one entry per step:
+        // first query row | 1 if the block is PARTIAL -- so that the main loop finds the next row
+        // offset with one LDS read issued a step ahead.
+        for (int seg0 = 0; seg0 < H_all; seg0 += kListMax) {
+            const int H = min(kListMax, H_all - seg0);
+            for (int i = tid; i < H; i += 256) {
+                const int u = H_all - 1 - (seg0 + i), pos = u / sub, sidx = u - pos * sub;
+                const int blk = pos < n_full ? full_idx[pos] : part_idx[pos - n_full];
+                s_steps[i] = (blk * a.Bq + sidx * TQ) | (pos >= n_full ? 1 : 0);
+                // loads are issued for one step past the end as well (into the free ring slot,
+                // never read): it repeats the last step's rows
+                if (i == H - 1) s_steps[H] = s_steps[i];
             }
-            read_rows(0, 0, rc_cur);
-        }
-
-        // ---- one step; SLOT = v % NBUF is compile-time so that every LDS access is "VGPR + immediate"
-        auto step = [&](int v, auto slot_tag) {
-            constexpr int SLOT = decltype(slot_tag)::value;
-            constexpr int NEXT = (SLOT + 1) & (NBUF - 1);
-            constexpr uint32_t q_cur = SLOT * 2 * (TILE * 2), do_cur = q_cur + TILE * 2;
-            constexpr uint32_t q_nxt = NEXT * 2 * (TILE * 2), do_nxt = q_nxt + TILE * 2;
-            f32x16& sacc = (SLOT & 1) ? s_odd : s_even;
-            f32x16& dpacc = (SLOT & 1) ? dp_odd : dp_even;
-            f32x16& s_nxt = (SLOT & 1) ? s_even : s_odd;
-            f32x16& dp_nxt = (SLOT & 1) ? dp_even : dp_odd;
-
-            // Step v+1 must have landed (it is read below), step v+2 may still be in flight; after the
-            // barrier nobody reads step v-1 any more and its slot takes step v+3.
-            __builtin_amdgcn_s_waitcnt(kWaitOlder);
             __syncthreads();
-            f32x4 nd[4];
-            read_rows(NEXT, 1, nd);                  // -delta of step v+1: dP starts from it
-            constexpr std::integral_constant<int, (SLOT + 3) & (NBUF - 1)> ld_slot{};
-            load_begin(ld_slot);
-            const bool partial = part_of[SLOT];
-            const int q_first = q0_of[SLOT] + 32 * qh;
+            int ld_v = 0;                           // step whose loads are issued next
+            int e_next = s_steps[0];
+            int q0_of[2];                           // first query row of the step in each ring slot,
+            bool part_of[2];                        // and whether its block is PARTIAL
 
-            u32x4 pk[2], dsk[2];
-            // four score elements at a time, stage by stage, so that no vector instruction has to
-            // wait for the one issued just before it
-            auto element_quad = [&](int c4) {
-                float sv[4], rcv[4], gr[4], pe[4], ds[4];
-                int dqk[4];
+            auto load_step = [&](auto slot_tag) {
+                constexpr int SLOT = decltype(slot_tag)::value;
+                const int e = __builtin_amdgcn_readfirstlane(e_next);
+                const int q0 = e & ~1;
+                q0_of[SLOT] = q0;
+                part_of[SLOT] = e & 1;
+                q_loader.start(q_rsrc, ring + SLOT * 2 * (TILE * 2), q0 * q_row_bytes);
+                do_loader.start(do_rsrc, ring + (SLOT * 2 + 1) * (TILE * 2), q0 * do_row_bytes);
+                dma_dword(row_rsrc, wave_row + SLOT * 2 * TQ * 4, lane * 4, q0 * 4);
+                e_next = s_steps[++ld_v];
+            };
+            // this lane's 16 row scalars of a step: rows 8 rg + 4 half + {0..3} of the wave's 32
+            auto read_rows = [&](int slot, int which, f32x4 (&out)[4]) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int r = 4 * c4 + i;
-                    sv[i] = sacc[r];
-                    rcv[i] = rc_cur[r >> 2][r & 3];
-                    // alibi / rel-bias need q - kv; the soft-cap and the plain score do not
-                    dqk[i] = (ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel) ? q_first + crow(r, half) - kv_lane : 0;
+                for (int rg = 0; rg < 4; ++rg)
+                    out[rg] = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(
+                        row_lds + (uint32_t)((slot * 2 + which) * TQ + 8 * rg) * 4);
+            };
+
+            load_step(std::integral_constant<int, 0>{});
+            wait_vmem();
+            __syncthreads();
+
+            // ---- one step; SLOT = v & 1 is compile-time so that every LDS access is "VGPR + immediate"
+            auto step = [&](auto slot_tag) {
+                constexpr int SLOT = decltype(slot_tag)::value;
+                constexpr uint32_t q_cur = SLOT * 2 * (TILE * 2), do_cur = q_cur + TILE * 2;
+                load_step(std::integral_constant<int, SLOT ^ 1>{});    // step v+1 (or the dummy past the end)
+                const bool partial = part_of[SLOT];
+                const int q_first = q0_of[SLOT] + 32 * x;
+
+                // scores
+                f32x4 nd[4], rcv4[4];
+                read_rows(SLOT, 1, nd);
+                f32x16 sacc, dpacc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    sacc[r] = 0.0f;
+                    dpacc[r] = nd[r >> 2][r & 3];    // dP - delta comes out of the accumulation
                 }
-                smod.p_with_grad4(sv, dqk, rcv, gr, pe);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ds[i] = pe[i] * gr[i];
-                pin4(ds);
+                for (int ks = 0; ks < NKS; ++ks) {
+                    sacc = mfma32(row_reader.read(q_cur, 0, ks), kf[ks], sacc);
+                    dpacc = mfma32(row_reader.read(do_cur, 0, ks), vf[ks], dpacc);
+                }
+                read_rows(SLOT, 0, rcv4);
+                u32x4 pk[2], dsk[2];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ds[i] *= dpacc[4 * c4 + i];
-                if (partial) {
-                    asm volatile("" ::: "memory");   // keep this a (scalar, rarely taken) branch
+                for (int c4 = 0; c4 < 4; ++c4) {
+                    float sv[4], rcv[4], gr[4], pe[4], ds[4];
+                    int dqk[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const MaskRow<MASK> mrow(a.p, b, hq, q_first + crow(4 * c4 + i, half));
-                        const bool keep = mrow(kv_lane);
-                        pe[i] = keep ? pe[i] : 0.0f;
-                        ds[i] = keep ? ds[i] : 0.0f;
+                        const int r = 4 * c4 + i;
+                        sv[i] = sacc[r];
+                        rcv[i] = rcv4[r >> 2][r & 3];
+                        // alibi / rel-bias need q - kv; the soft-cap and the plain score do not
+                        dqk[i] = (ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel) ? q_first + crow(r, half) - kv_lane : 0;
+                    }
+                    smod.p_with_grad4(sv, dqk, rcv, gr, pe);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) ds[i] = pe[i] * gr[i] * dpacc[4 * c4 + i];
+                    if (partial) {
+                        asm volatile("" ::: "memory");   // keep this a (scalar, rarely taken) branch
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const MaskRow<MASK> mrow(a.p, b, hq, q_first + crow(4 * c4 + i, half));
+                            const bool keep = mrow(kv_lane);
+                            pe[i] = keep ? pe[i] : 0.0f;
+                            ds[i] = keep ? ds[i] : 0.0f;
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const int e = 2 * c4 + i;
+                        pk[e >> 2][e & 3] = pack_bf16(pe[2 * i], pe[2 * i + 1]);
+                        dsk[e >> 2][e & 3] = pack_bf16(ds[2 * i], ds[2 * i + 1]);
                     }
                 }
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int e = 2 * c4 + i;
-                    pk[e >> 2][e & 3] = pack_bf16(pe[2 * i], pe[2 * i + 1]);
-                    dsk[e >> 2][e & 3] = pack_bf16(ds[2 * i], ds[2 * i + 1]);
-                }
-            };
-            constexpr int N1 = 2 * NKS, N3H = 2 * NDB, NM = N1 + 2 * N3H;
-            auto frag_load = [&](int m) {
-                if (m < N1) return (m & 1) ? read_row(do_nxt, 0, m >> 1) : read_row(q_nxt, 0, m >> 1);
-                const int j = m - N1, c = j / N3H, jj = j % N3H;
-                return (jj & 1) ? read_tr(q_cur, 16 * c, jj >> 1) : read_tr(do_cur, 16 * c, jj >> 1);
-            };
-            auto mfma_op = [&](int m, bf16x8 fr) {
-                if (m < N1) {
-                    if (m == 0) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) s_nxt[r] = 0.0f;
-                    }
-                    if (m == 1) dp_nxt = as_acc(nd);
-                    if (m & 1) dp_nxt = mfma32(fr, vf[m >> 1], dp_nxt);
-                    else s_nxt = mfma32(fr, kf[m >> 1], s_nxt);
-                } else {
-                    const int j = m - N1, c = j / N3H, jj = j % N3H;
-                    if (jj & 1) dk[jj >> 1] = mfma32(fr, __builtin_bit_cast(bf16x8, dsk[c]), dk[jj >> 1]);
-                    else dv[jj >> 1] = mfma32(fr, __builtin_bit_cast(bf16x8, pk[c]), dv[jj >> 1]);
-                }
-            };
-            constexpr int PF = 3;                    // operand fragments are read PF MFMAs ahead
-            constexpr DkdvSchedule<D> kSched = DkdvSchedule<D>::make();
-            bf16x8 fr[NM];
-#pragma unroll
-            for (int sq = 0; sq < PF; ++sq) fr[kSched.order[sq]] = frag_load(kSched.order[sq]);
-            static_for<0, kSched.NCHUNK>([&](auto chunk_tag) {
-                constexpr int i = decltype(chunk_tag)::value;
-                // this chunk's share of the loads of step v+3
-                static_for<i * kLoads / kSched.NCHUNK, (i + 1) * kLoads / kSched.NCHUNK>(
-                    [&](auto piece_tag) { load_piece(ld_slot, piece_tag); });
-#pragma unroll
-                for (int sq = kSched.begin[i]; sq < kSched.begin[i + 1]; ++sq) {
-                    if (sq + PF < NM) fr[kSched.order[sq + PF]] = frag_load(kSched.order[sq + PF]);
-                    mfma_op(kSched.order[sq], fr[kSched.order[sq]]);
-                }
-                if (i < 4) element_quad(i);
-                if (i == kSched.NCHUNK - 1) read_rows(NEXT, 0, rc_cur);   // for the next step's elements
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        };
 
-        int v = 0;
-        for (; v + 3 < H; v += 4) {
-            step(v, std::integral_constant<int, 0>{});
-            step(v + 1, std::integral_constant<int, 1>{});
-            step(v + 2, std::integral_constant<int, 2>{});
-            step(v + 3, std::integral_constant<int, 3>{});
-        }
-        if (v < H) step(v, std::integral_constant<int, 0>{});
-        if (v + 1 < H) step(v + 1, std::integral_constant<int, 1>{});
-        if (v + 2 < H) step(v + 2, std::integral_constant<int, 2>{});
-        wait_vmem();
-        __syncthreads();                // before the next segment, head or the reduction reuses the LDS
-      }
-    }
+                // exchange: keep what this wave's output needs, hand over the other
+                u32x4 own[2];
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    own[c] = x ? dsk[c] : pk[c];
+                    *(__attribute__((address_space(3))) u32x4*)(uintptr_t)(xchg_mine + c * 1024) = x ? pk[c] : dsk[c];
+                }
+                __syncthreads();
+                u32x4 theirs[2];
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+                    theirs[c] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(xchg_theirs + c * 1024);
 
-    // ---- add the two query-halves through LDS and write dK, dV (bf16)
-    float* red = (float*)smem;          // [key block][dK | dV][D][32 keys] floats
-    if (qh == 1) {
+                // outputs: contraction over this wave's own 32 rows, then over its partner's
+                constexpr uint32_t slot_off = SLOT * 2 * (TILE * 2);
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
+                for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                red[((kb * 2 + 0) * D + db * 32 + crow(r, half)) * 32 + l32] = dk[db][r];
-                red[((kb * 2 + 1) * D + db * 32 + crow(r, half)) * 32 + l32] = dv[db][r];
+                    for (int db = 0; db < NDB; ++db)
+                        acc[db] = mfma32(tr_own.read(slot_off, 16 * c, db), __builtin_bit_cast(bf16x8, own[c]), acc[db]);
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db)
+                        acc[db] = mfma32(tr_other.read(slot_off, 16 * c, db), __builtin_bit_cast(bf16x8, theirs[c]), acc[db]);
+                wait_vmem();
+                __syncthreads();
+            };
+
+            int v = 0;
+            for (; v + 1 < H; v += 2) {
+                step(std::integral_constant<int, 0>{});
+                step(std::integral_constant<int, 1>{});
             }
+            if (v < H) step(std::integral_constant<int, 0>{});
+        }
     }
-    __syncthreads();
-    if (qh == 0) {
-        const float kscale = a.scale * ScoreMod<SCORE>::grad_scale();
-        bf16* dkp = a.dK + b * a.dk_sb + hkv * a.dk_sh + (int64_t)kv_lane * a.dk_ss;
-        bf16* dvp = a.dV + b * a.dv_sb + hkv * a.dv_sh + (int64_t)kv_lane * a.dv_ss;
+
+    // ---- dV (x = 0) or dK (x = 1, with the scale and the score_mod's gradient factor), bf16
+    {
+        const float oscale = x ? a.scale * ScoreMod<SCORE>::grad_scale() : 1.0f;
+        bf16* op = x ? a.dK + b * a.dk_sb + hkv * a.dk_sh + (int64_t)kv_lane * a.dk_ss
+                     : a.dV + b * a.dv_sb + hkv * a.dv_sh + (int64_t)kv_lane * a.dv_ss;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
-                float k4[4], v4[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int r = 4 * rg + e;
-                    k4[e] = (dk[db][r] + red[((kb * 2 + 0) * D + db * 32 + crow(r, half)) * 32 + l32]) * kscale;
-                    v4[e] = dv[db][r] + red[((kb * 2 + 1) * D + db * 32 + crow(r, half)) * 32 + l32];
-                }
-                u32x2 ko, vo;
-                ko[0] = pack_bf16(k4[0], k4[1]);
-                ko[1] = pack_bf16(k4[2], k4[3]);
-                vo[0] = pack_bf16(v4[0], v4[1]);
-                vo[1] = pack_bf16(v4[2], v4[3]);
-                *(u32x2*)(dkp + db * 32 + 8 * rg + 4 * half) = ko;
-                *(u32x2*)(dvp + db * 32 + 8 * rg + 4 * half) = vo;
+                u32x2 o;
+                o[0] = pack_bf16(acc[db][4 * rg] * oscale, acc[db][4 * rg + 1] * oscale);
+                o[1] = pack_bf16(acc[db][4 * rg + 2] * oscale, acc[db][4 * rg + 3] * oscale);
+                *(u32x2*)(op + db * 32 + 8 * rg + 4 * half) = o;
             }
     }
 }
