@@ -111,6 +111,19 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
     __shared__ __attribute__((aligned(256))) float s_row[2][2][TQ];           // [slot][rc | -delta][row]
     constexpr int kListMax = 1024;
     __shared__ int s_steps[kListMax + 2];          // the walk of the current head, see below
+#ifdef FLEXATTN_TRACE
+    __shared__ unsigned long long s_trace[16 * 16];
+    int tv = 0;
+#define TRACE_STAMP(k)                                                              \
+    do {                                                                            \
+        if (blockIdx.x == FLEXATTN_TRACE && w == 0 && tv >= 8 && tv < 24) {         \
+            const unsigned long long t_ = __builtin_readcyclecounter();            \
+            if (lane == 0) s_trace[(tv - 8) * 16 + (k)] = t_;                       \
+        }                                                                           \
+    } while (0)
+#else
+#define TRACE_STAMP(k)
+#endif
 
     // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
     const int units = a.B * a.Hkv;
@@ -199,16 +212,30 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
             int q0_of[2];                           // first query row of the step in each ring slot,
             bool part_of[2];                        // and whether its block is PARTIAL
 
-            auto load_step = [&](auto slot_tag) {
+            int ld_q0 = 0;                          // first row of the step being loaded
+            constexpr int kLoads = 2 * Loader::NI + 1;      // load instructions per wave and step
+            auto load_begin = [&](auto slot_tag) {
                 constexpr int SLOT = decltype(slot_tag)::value;
                 const int e = __builtin_amdgcn_readfirstlane(e_next);
-                const int q0 = e & ~1;
-                q0_of[SLOT] = q0;
+                ld_q0 = e & ~1;
+                q0_of[SLOT] = ld_q0;
                 part_of[SLOT] = e & 1;
-                q_loader.start(q_rsrc, ring + SLOT * 2 * (TILE * 2), q0 * q_row_bytes);
-                do_loader.start(do_rsrc, ring + (SLOT * 2 + 1) * (TILE * 2), q0 * do_row_bytes);
-                dma_dword(row_rsrc, wave_row + SLOT * 2 * TQ * 4, lane * 4, q0 * 4);
                 e_next = s_steps[++ld_v];
+            };
+            // piece P of the loads of a step: NI for the Q tile, NI for the dO tile, one row of scalars
+            auto load_piece = [&](auto slot_tag, auto piece_tag) {
+                constexpr int SLOT = decltype(slot_tag)::value, P = decltype(piece_tag)::value;
+                if constexpr (P < Loader::NI)
+                    q_loader.template start_one<P>(q_rsrc, ring + SLOT * 2 * (TILE * 2), ld_q0 * q_row_bytes);
+                else if constexpr (P < 2 * Loader::NI)
+                    do_loader.template start_one<P - Loader::NI>(do_rsrc, ring + (SLOT * 2 + 1) * (TILE * 2),
+                                                                 ld_q0 * do_row_bytes);
+                else
+                    dma_dword(row_rsrc, wave_row + SLOT * 2 * TQ * 4, lane * 4, ld_q0 * 4);
+            };
+            auto load_step = [&](auto slot_tag) {   // all at once (prologue)
+                load_begin(slot_tag);
+                static_for<0, kLoads>([&](auto piece_tag) { load_piece(slot_tag, piece_tag); });
             };
             // this lane's 16 row scalars of a step: rows 8 rg + 4 half + {0..3} of the wave's 32
             auto read_rows = [&](int slot, int which, f32x4 (&out)[4]) {
@@ -226,7 +253,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
             auto step = [&](auto slot_tag) {
                 constexpr int SLOT = decltype(slot_tag)::value;
                 constexpr uint32_t q_cur = SLOT * 2 * (TILE * 2), do_cur = q_cur + TILE * 2;
-                load_step(std::integral_constant<int, SLOT ^ 1>{});    // step v+1 (or the dummy past the end)
+                TRACE_STAMP(0);
+                // step v+1 (or the dummy past the end); its loads are issued between the MFMAs below: a
+                // wave waits on every load instruction until the memory pipe has taken it
+                constexpr std::integral_constant<int, SLOT ^ 1> ld_slot{};
+                load_begin(ld_slot);
+                TRACE_STAMP(1);
                 const bool partial = part_of[SLOT];
                 const int q_first = q0_of[SLOT] + 32 * x;
 
@@ -239,11 +271,24 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                     sacc[r] = 0.0f;
                     dpacc[r] = nd[r >> 2][r & 3];    // dP - delta comes out of the accumulation
                 }
+                {   // operand fragments are read PF MFMAs ahead of their use
+                    constexpr int NM = 2 * NKS, PF = 4;
+                    auto frag = [&](int m) { return row_reader.read((m & 1) ? do_cur : q_cur, 0, m >> 1); };
+                    bf16x8 fr[NM];
 #pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) {
-                    sacc = mfma32(row_reader.read(q_cur, 0, ks), kf[ks], sacc);
-                    dpacc = mfma32(row_reader.read(do_cur, 0, ks), vf[ks], dpacc);
+                    for (int m = 0; m < PF; ++m) fr[m] = frag(m);
+                    static_for<0, NM>([&](auto m_tag) {
+                        constexpr int m = decltype(m_tag)::value;
+                        if constexpr (m + PF < NM) fr[m + PF] = frag(m + PF);
+                        if (m & 1) dpacc = mfma32(fr[m], vf[m >> 1], dpacc);
+                        else sacc = mfma32(fr[m], kf[m >> 1], sacc);
+                        static_for<0, kLoads>([&](auto piece_tag) {
+                            if constexpr (decltype(piece_tag)::value * NM / kLoads == m) load_piece(ld_slot, piece_tag);
+                        });
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
                 }
+                TRACE_STAMP(2);
                 read_rows(SLOT, 0, rcv4);
                 u32x4 pk[2], dsk[2];
 #pragma unroll
@@ -279,6 +324,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                     }
                 }
 
+                TRACE_STAMP(3);
                 // exchange: keep what this wave's output needs, hand over the other
                 u32x4 own[2];
 #pragma unroll
@@ -286,26 +332,39 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                     own[c] = x ? dsk[c] : pk[c];
                     *(__attribute__((address_space(3))) u32x4*)(uintptr_t)(xchg_mine + c * 1024) = x ? pk[c] : dsk[c];
                 }
-                __syncthreads();
+                // outputs: contraction over this wave's own 32 rows (while the exchange settles), then,
+                // after the barrier, over its partner's
+                constexpr uint32_t slot_off = SLOT * 2 * (TILE * 2);
+                constexpr int NMH = 2 * NDB, PF = 4;          // MFMAs per half: [slice c][block db]
                 u32x4 theirs[2];
+                auto out_half = [&](const TrReader<D>& reader, const u32x4 (&bop)[2]) {
+                    auto frag = [&](int m) { return reader.read(slot_off, 16 * (m / NDB), m % NDB); };
+                    bf16x8 fr[NMH];
+#pragma unroll
+                    for (int m = 0; m < PF; ++m) fr[m] = frag(m);
+#pragma unroll
+                    for (int m = 0; m < NMH; ++m) {
+                        if (m + PF < NMH) fr[m + PF] = frag(m + PF);
+                        acc[m % NDB] = mfma32(fr[m], __builtin_bit_cast(bf16x8, bop[m / NDB]), acc[m % NDB]);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                };
+                out_half(tr_own, own);
+                TRACE_STAMP(4);
+                __syncthreads();
+                TRACE_STAMP(5);
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
                     theirs[c] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(xchg_theirs + c * 1024);
-
-                // outputs: contraction over this wave's own 32 rows, then over its partner's
-                constexpr uint32_t slot_off = SLOT * 2 * (TILE * 2);
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-#pragma unroll
-                    for (int db = 0; db < NDB; ++db)
-                        acc[db] = mfma32(tr_own.read(slot_off, 16 * c, db), __builtin_bit_cast(bf16x8, own[c]), acc[db]);
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-#pragma unroll
-                    for (int db = 0; db < NDB; ++db)
-                        acc[db] = mfma32(tr_other.read(slot_off, 16 * c, db), __builtin_bit_cast(bf16x8, theirs[c]), acc[db]);
+                out_half(tr_other, theirs);
+                TRACE_STAMP(6);
                 wait_vmem();
+                TRACE_STAMP(7);
                 __syncthreads();
+                TRACE_STAMP(8);
+#ifdef FLEXATTN_TRACE
+                ++tv;
+#endif
             };
 
             int v = 0;
@@ -317,6 +376,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
         }
     }
 
+#ifdef FLEXATTN_TRACE
+    __syncthreads();
+    if (blockIdx.x == FLEXATTN_TRACE && tid < 16 * 16)
+        ((unsigned long long*)(a.lse2 + (int64_t)a.B * a.Hq * a.q_len))[tid] = s_trace[tid];
+#endif
     // ---- dV (x = 0) or dK (x = 1, with the scale and the score_mod's gradient factor), bf16
     {
         const float oscale = x ? a.scale * ScoreMod<SCORE>::grad_scale() : 1.0f;
