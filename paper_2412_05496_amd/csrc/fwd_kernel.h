@@ -108,17 +108,20 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     const RowReader<D> k_reader(l32, half);
     const TrReader<D> v_reader(lane);
 
-    // S^T = K Q^T for the two 32-key blocks of the K tile in buffer BUF (compile-time)
-    auto qk = [&](auto buf_tag, f32x16 (&s)[2]) {
+    // S^T = K Q^T for the two 32-key blocks of the K tile in buffer BUF (compile-time);
+    // between(m) runs after the m-th of the 2 D / 16 MFMAs (used to spread out tile loads)
+    auto qk = [&](auto buf_tag, f32x16 (&s)[2], auto&& between) {
         constexpr int BUF = decltype(buf_tag)::value;
+        constexpr int NKS = D / 16;
+        static_for<0, 2 * NKS>([&](auto m_tag) {
+            constexpr int m = decltype(m_tag)::value, kvb = m / NKS, ks = m % NKS;
+            if constexpr (ks == 0) {
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kvb][r] = 0.0f;
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks)
-                s[kvb] = mfma32(k_reader.read(smem_bytes + BUF * (TILE * 2), kvb * 32, ks), qf[ks], s[kvb]);
-        }
+                for (int r = 0; r < 16; ++r) s[kvb][r] = 0.0f;
+            }
+            s[kvb] = mfma32(k_reader.read(smem_bytes + BUF * (TILE * 2), kvb * 32, ks), qf[ks], s[kvb]);
+            between(m_tag);
+        });
     };
 
     f32x16 oacc[D / 32];
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     wait_vmem();
     __syncthreads();
     f32x16 s_cur[2], s_next[2];
-    qk(std::integral_constant<int, 0>{}, s_cur);
+    qk(std::integral_constant<int, 0>{}, s_cur, [](auto) {});
 
     // One tile (t & 1 == BUF).  S^T of tile t+1 (MFMA) is issued next to the softmax of tile t (VALU),
     // P V of the first 32 keys next to the softmax of the second 32.
@@ -216,15 +219,31 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
         // nobody still reads K(t) [buffer BUF] or V(t-1) [buffer BUF ^ 1], which are refilled next.
         wait_vmem();
         __syncthreads();
-        if (t + 2 < T) {
-            kv_t2 = walk.next(part_t2);
-            load_k(BUF, kv_t2);
-        }
-        if constexpr (HAS_NEXT) load_v(BUF ^ 1, kv_t1);
+        // K(t+2) and V(t+1) are loaded piece by piece between the MFMAs of S^T(t+1): a wave waits on
+        // every load instruction until the memory pipe has taken it, and a burst of them from all
+        // waves at once keeps everybody waiting
+        const bool ld_k = t + 2 < T;
+        if (ld_k) kv_t2 = walk.next(part_t2);
         const int kv0 = kv_t;
         const bool partial = part_t;
         bf16x8 pf[2];
-        if constexpr (HAS_NEXT) qk(std::integral_constant<int, BUF ^ 1>{}, s_next);
+        if constexpr (HAS_NEXT) {
+            using L = WaveTileLoader<D, NW>;
+            constexpr int NP = 2 * L::NI, NMQ = 2 * (D / 16);
+            qk(std::integral_constant<int, BUF ^ 1>{}, s_next, [&](auto m_tag) {
+                static_for<0, NP>([&](auto p_tag) {
+                    constexpr int p = decltype(p_tag)::value;
+                    if constexpr (p * NMQ / NP == decltype(m_tag)::value) {
+                        if constexpr (p < L::NI) {
+                            if (ld_k) k_loader.template start_one<p>(k_rsrc, smem_bytes + BUF * (TILE * 2), kv_t2 * k_row_bytes);
+                        } else {
+                            v_loader.template start_one<p - L::NI>(v_rsrc, smem_bytes + (2 + (BUF ^ 1)) * (TILE * 2),
+                                                                   kv_t1 * v_row_bytes);
+                        }
+                    }
+                });
+            });
+        }
         softmax(s_cur[0], kv0, partial, pf);
         pv(buf_tag, 0, pf);
         softmax(s_cur[1], kv0 + 32, partial, pf);
