@@ -476,25 +476,53 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
         constexpr int BUF = decltype(buf_tag)::value;
         const int kv0_cur = kv0;
         const bool partial = part_next;
-        if (t + 1 < T) {
-            kv0 = walk.next(part_next);
-            load_tiles(BUF ^ 1, kv0);        // buffer BUF ^ 1 was last read in step t-1
-        }
+        // K(t+1), V(t+1) go to buffer BUF ^ 1, last read in step t-1.  Their loads are issued piece by
+        // piece between the first MFMAs below: a wave waits on every load instruction until the
+        // memory pipe has taken it.
+        const bool ld = t + 1 < T;
+        if (ld) kv0 = walk.next(part_next);
         constexpr uint32_t kt = BUF * (TILE * 2), vt = (2 + BUF) * (TILE * 2);
+        using L = WaveTileLoader<D, NW>;
+        constexpr int NKS = D / 16, NDB = D / 32, PF = 4;
 
-#pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb) {
-            // S^T = K Q^T and dP^T = V dO^T for 32 keys
+        static_for<0, 2>([&](auto kvb_tag) {
+            constexpr int kvb = decltype(kvb_tag)::value;
+            // S^T = K Q^T and dP^T = V dO^T for 32 keys; operand fragments read PF MFMAs ahead
             f32x16 sacc, dpacc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 sacc[r] = 0.0f;
                 dpacc[r] = neg_delta;        // dP - delta comes out of the accumulation
             }
+            {
+                constexpr int NM = 2 * NKS, NP = 2 * L::NI;
+                auto frag = [&](int m) { return row_reader.read((m & 1) ? vt : kt, kvb * 32, m >> 1); };
+                bf16x8 fr[NM];
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(row_reader.read(kt, kvb * 32, ks), qf[ks], sacc);
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(row_reader.read(vt, kvb * 32, ks), dof[ks], dpacc);
+                for (int m = 0; m < PF; ++m) fr[m] = frag(m);
+                static_for<0, NM>([&](auto m_tag) {
+                    constexpr int m = decltype(m_tag)::value;
+                    if constexpr (m + PF < NM) fr[m + PF] = frag(m + PF);
+                    if (m & 1) dpacc = mfma32(fr[m], dof[m >> 1], dpacc);
+                    else sacc = mfma32(fr[m], qf[m >> 1], sacc);
+                    if constexpr (kvb == 0) {
+                        static_for<0, NP>([&](auto p_tag) {
+                            constexpr int p = decltype(p_tag)::value;
+                            if constexpr (p * NM / NP == m) {
+                                if (ld) {
+                                    if constexpr (p < L::NI)
+                                        k_loader.template start_one<p>(k_rsrc, lds_addr(smem) + (BUF ^ 1) * (TILE * 2),
+                                                                       kv0 * k_row_bytes);
+                                    else
+                                        v_loader.template start_one<p - L::NI>(
+                                            v_rsrc, lds_addr(smem) + (2 + (BUF ^ 1)) * (TILE * 2), kv0 * v_row_bytes);
+                                }
+                            }
+                        });
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int kv = kv0_cur + kvb * 32 + crow(r, half);
@@ -508,16 +536,25 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
                 for (int r = 0; r < 16; ++r) dpacc[r] = mrow(kv0_cur + kvb * 32 + crow(r, half)) ? dpacc[r] : 0.0f;
             }
             // dQ^T += K^T dS^T
+            u32x4 dsk[2];
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                u32x4 dsk;
+            for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) dsk[jj] = pack_bf16(dpacc[8 * c + 2 * jj], dpacc[8 * c + 2 * jj + 1]);
+                for (int jj = 0; jj < 4; ++jj) dsk[c][jj] = pack_bf16(dpacc[8 * c + 2 * jj], dpacc[8 * c + 2 * jj + 1]);
+            {
+                constexpr int NM = 2 * NDB;              // [slice c][block db]
+                auto frag = [&](int m) { return tr_reader.read(kt, kvb * 32 + 16 * (m / NDB), m % NDB); };
+                bf16x8 fr[NM];
 #pragma unroll
-                for (int db = 0; db < D / 32; ++db)
-                    dq[db] = mfma32(tr_reader.read(kt, kvb * 32 + 16 * c, db), __builtin_bit_cast(bf16x8, dsk), dq[db]);
+                for (int m = 0; m < PF; ++m) fr[m] = frag(m);
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    if (m + PF < NM) fr[m + PF] = frag(m + PF);
+                    dq[m % NDB] = mfma32(fr[m], __builtin_bit_cast(bf16x8, dsk[m / NDB]), dq[m % NDB]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-        }
+        });
         wait_vmem();
         __syncthreads();
     };
