@@ -44,6 +44,13 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
+// acc + lo(pair) + hi(pair) for a packed pair of bf16 values (v_dot2c_f32_bf16).
+__device__ __forceinline__ float pair_sum_bf16(uint32_t pair, float acc) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair), __builtin_bit_cast(bf16x2_t, 0x3f803f80u),
+                                           acc, false);
+}
+
 // Load of read-only data at a wave-uniform address: constant address space, so the compiler may
 // use the scalar cache and keep the load off the vector memory counter.
 __device__ __forceinline__ int32_t ldc(const int32_t* p) {

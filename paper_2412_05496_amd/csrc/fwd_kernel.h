@@ -173,18 +173,20 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
                     for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
             }
         }
-        float psum = 0.0f;
+        // The row sum adds up the bf16-rounded probabilities, the values P V is computed from, two at
+        // a time (dot product of a packed pair with (1, 1), fp32 accumulation).
+        float psum[2] = {0.0f, 0.0f};
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             u32x4 pk;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
-                psum += s[8 * c + 2 * jj] + s[8 * c + 2 * jj + 1];
                 pk[jj] = pack_bf16(s[8 * c + 2 * jj], s[8 * c + 2 * jj + 1]);
+                psum[jj & 1] = pair_sum_bf16(pk[jj], psum[jj & 1]);
             }
             pf[c] = __builtin_bit_cast(bf16x8, pk);
         }
-        l_run += psum;
+        l_run += psum[0] + psum[1];
     };
 
     // O^T += V^T P^T for the 32-key block kvb (compile-time) of the V tile in buffer BUF
