@@ -111,19 +111,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
     __shared__ __attribute__((aligned(256))) float s_row[2][2][TQ];           // [slot][rc | -delta][row]
     constexpr int kListMax = 1024;
     __shared__ int s_steps[kListMax + 2];          // the walk of the current head, see below
-#ifdef FLEXATTN_TRACE
-    __shared__ unsigned long long s_trace[16 * 16];
-    int tv = 0;
-#define TRACE_STAMP(k)                                                              \
-    do {                                                                            \
-        if (blockIdx.x == FLEXATTN_TRACE && w == 0 && tv >= 8 && tv < 24) {         \
-            const unsigned long long t_ = __builtin_readcyclecounter();            \
-            if (lane == 0) s_trace[(tv - 8) * 16 + (k)] = t_;                       \
-        }                                                                           \
-    } while (0)
-#else
-#define TRACE_STAMP(k)
-#endif
 
     // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
     const int units = a.B * a.Hkv;
@@ -253,12 +240,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
             auto step = [&](auto slot_tag) {
                 constexpr int SLOT = decltype(slot_tag)::value;
                 constexpr uint32_t q_cur = SLOT * 2 * (TILE * 2), do_cur = q_cur + TILE * 2;
-                TRACE_STAMP(0);
                 // step v+1 (or the dummy past the end); its loads are issued between the MFMAs below: a
                 // wave waits on every load instruction until the memory pipe has taken it
                 constexpr std::integral_constant<int, SLOT ^ 1> ld_slot{};
                 load_begin(ld_slot);
-                TRACE_STAMP(1);
                 const bool partial = part_of[SLOT];
                 const int q_first = q0_of[SLOT] + 32 * x;
 
@@ -288,7 +273,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                         __builtin_amdgcn_sched_barrier(0);
                     });
                 }
-                TRACE_STAMP(2);
                 read_rows(SLOT, 0, rcv4);
                 u32x4 pk[2], dsk[2];
 #pragma unroll
@@ -323,8 +307,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                         dsk[e >> 2][e & 3] = pack_bf16(ds[2 * i], ds[2 * i + 1]);
                     }
                 }
-
-                TRACE_STAMP(3);
                 // exchange: keep what this wave's output needs, hand over the other
                 u32x4 own[2];
 #pragma unroll
@@ -350,21 +332,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                     }
                 };
                 out_half(tr_own, own);
-                TRACE_STAMP(4);
                 __syncthreads();
-                TRACE_STAMP(5);
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
                     theirs[c] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(xchg_theirs + c * 1024);
                 out_half(tr_other, theirs);
-                TRACE_STAMP(6);
                 wait_vmem();
-                TRACE_STAMP(7);
                 __syncthreads();
-                TRACE_STAMP(8);
-#ifdef FLEXATTN_TRACE
-                ++tv;
-#endif
             };
 
             int v = 0;
@@ -376,11 +350,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
         }
     }
 
-#ifdef FLEXATTN_TRACE
-    __syncthreads();
-    if (blockIdx.x == FLEXATTN_TRACE && tid < 16 * 16)
-        ((unsigned long long*)(a.lse2 + (int64_t)a.B * a.Hq * a.q_len))[tid] = s_trace[tid];
-#endif
     // ---- dV (x = 0) or dK (x = 1, with the scale and the score_mod's gradient factor), bf16
     {
         const float oscale = x ? a.scale * ScoreMod<SCORE>::grad_scale() : 1.0f;

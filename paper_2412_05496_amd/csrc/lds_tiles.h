@@ -78,6 +78,13 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* p, uint32_t bytes) {
                  __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
 }
 
+// The descriptor as four values the compiler knows to be scalar (an "s" operand that it believes
+// to live in vector registers is not moved for us).
+__device__ __forceinline__ i32x4 scalar_rsrc(i32x4 r) {
+    return i32x4{__builtin_amdgcn_readfirstlane(r[0]), __builtin_amdgcn_readfirstlane(r[1]),
+                 __builtin_amdgcn_readfirstlane(r[2]), __builtin_amdgcn_readfirstlane(r[3])};
+}
+
 // LDS-DMA loads are issued from inline assembly on purpose.  When the compiler sees such a load it
 // makes every later LDS read that it cannot prove disjoint wait for vmcnt(0), which serialises the
 // prefetch with the compute it is meant to overlap; completion is tracked by hand instead
@@ -89,7 +96,7 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* p, uint32_t bytes) {
 // dma_dword: 64 lanes x 4 bytes to `lds` .. +256.
 __device__ __forceinline__ void dma_dword(i32x4 rsrc, uint32_t lds, int voff, int soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(voff), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
 // dma_x4 / dma_x2: four (two) 1 KiB loads to `lds` + 0, 1024, 2048, 3072.  The immediate offset
@@ -101,18 +108,18 @@ __device__ __forceinline__ void dma_x4(i32x4 rsrc, uint32_t lds, int v0, int v1,
                  "buffer_load_dwordx4 %2, %5, %6 offen offset:1024 lds\n\t"
                  "buffer_load_dwordx4 %3, %5, %6 offen offset:2048 lds\n\t"
                  "buffer_load_dwordx4 %4, %5, %6 offen offset:3072 lds"
-                 :: "s"(lds), "v"(v0), "v"(v1), "v"(v2), "v"(v3), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(v0), "v"(v1), "v"(v2), "v"(v3), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 __device__ __forceinline__ void dma_x2(i32x4 rsrc, uint32_t lds, int v0, int v1, int soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\t"
                  "buffer_load_dwordx4 %1, %3, %4 offen lds\n\t"
                  "buffer_load_dwordx4 %2, %3, %4 offen offset:1024 lds"
-                 :: "s"(lds), "v"(v0), "v"(v1), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(v0), "v"(v1), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
 __device__ __forceinline__ void dma_x1(i32x4 rsrc, uint32_t lds, int v0, int soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(lds), "v"(v0), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(v0), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
 // The tile copy with buffer loads, for a workgroup of NW waves: the row of the tile is selected by
