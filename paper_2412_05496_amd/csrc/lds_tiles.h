@@ -209,32 +209,34 @@ struct TrReader {
 };
 
 // Walk over the 64-wide tiles of the blocks a BlockMask lists for one row (or column) of blocks:
-// FULL blocks first, then PARTIAL ones, each block cut into `sub` tiles.  The block index of the
-// following block is fetched (scalar cache) when the walk enters a block, i.e. ahead of its use.
+// FULL blocks first, then PARTIAL ones, each block cut into `sub` tiles.  Written without
+// branches, and the index of the following block is fetched (scalar cache) on every call and only
+// consumed by the call after it, so that the fetch has a tile's worth of work to hide behind.
 struct TileWalk {
     const int32_t* full_idx;
     const int32_t* part_idx;
     int n_full, n_blocks, sub, block_len;
-    int pos, s, blk;
+    int pos, s, blk, fetched;
+    bool entered;                               // the previous call moved on to the next block
     __device__ __forceinline__ int block_at(int p) const {
-        return p < n_full ? ldc(full_idx + p) : ldc(part_idx + (p - n_full));
+        return ldc(p < n_full ? full_idx + p : part_idx + (p - n_full));
     }
     __device__ __forceinline__ TileWalk(const int32_t* full_idx_, const int32_t* part_idx_, int n_full_, int n_part,
                                         int sub_, int block_len_)
         : full_idx(full_idx_), part_idx(part_idx_), n_full(n_full_), n_blocks(n_full_ + n_part), sub(sub_),
-          block_len(block_len_), pos(0), s(0) {
+          block_len(block_len_), pos(0), s(0), fetched(0), entered(false) {
         blk = n_blocks > 0 ? block_at(0) : 0;
     }
     // first row (column) of the next tile, and whether its block is PARTIAL; must not be called
     // more than n_blocks * sub times
     __device__ __forceinline__ int next(bool& partial) {
+        blk = entered ? fetched : blk;
         const int x0 = blk * block_len + s * 64;
         partial = pos >= n_full;
-        if (++s == sub) {
-            s = 0;
-            ++pos;
-            blk = pos < n_blocks ? block_at(pos) : 0;
-        }
+        fetched = block_at(min(pos + 1, n_blocks - 1));
+        entered = s + 1 == sub;
+        s = entered ? 0 : s + 1;
+        pos += entered ? 1 : 0;
         return x0;
     }
 };
