@@ -94,7 +94,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
 
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
     const MaskRow<MASK> mrow(a.p, b, hq, q_row);
-    const float neg2c = -2.0f * smod.capl2;
+    const float inv_neg2c = smod.capl2 > 0.0f ? -0.5f / smod.capl2 : 0.0f;   // 1 / (-2 cap log2 e)
 
     // first key and PARTIAL flag of tiles t, t+1, t+2 (the walk is always two tiles ahead)
     TileWalk walk(a.full_idx + line * a.NC, a.kv_idx + line * a.NC, n_full, n_part, a.sub, a.Bk);
@@ -139,9 +139,13 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     auto softmax = [&](f32x16& s, int kvs, bool partial, bf16x8 (&pf)[2]) {
         const int dq_base = q_row - kvs;
         if constexpr (BOUNDED) {
-            // p = 2^(x - cap log2 e) = 2^(-2 cap log2 e * r): no maximum to track
+            // p = 2^(x - cap log2 e) = 2^(-2 cap log2 e * r), r = 1 / (1 + e): no maximum to track
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(neg2c * smod.cap_r(s[r], dq_base - crow(r, half)));
+            for (int r = 0; r < 16; ++r) {
+                // -2 cap log2e / (1 + e) as ONE reciprocal: rcp((1 + e) / (-2 cap log2e))
+                const float e = fast_exp2(smod.pre(s[r], dq_base - crow(r, half)));
+                s[r] = fast_exp2(fast_rcp(__builtin_fmaf(e, inv_neg2c, inv_neg2c)));
+            }
             if (partial) {
                 asm volatile("" ::: "memory");   // keep this a branch, not 16 selects on every tile
 #pragma unroll
