@@ -30,6 +30,17 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
+def measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+    same command (scaled by the copy-kernel calibration); the figures and the commands that produced
+    them are in profiles/.  None if no figure is recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        return json.load(f).get(kernel, {}).get("bytes")
+
+
 def event_time_ms(fn, iters: int) -> float:
     """Average duration of fn() in ms, bracketed by events on the current (launch) stream."""
     import torch
@@ -134,7 +145,7 @@ def main() -> int:
     dom = max(alg, key=lambda k: kt[k])
     achieved = alg[dom] / (kt[dom] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(dom),
                 "avg_ms": round(kt[dom], 4)}
     bwd_ms = kt["bwd_delta"] + kt["bwd_dkdv"] + kt["bwd_dq"]
     out = {
@@ -181,7 +192,7 @@ def main() -> int:
             "value": round(gbs, 1), "unit": "GB/s",
             "roofline": {"kernel": "decode_split+combine", "bound": "hbm", "achieved": round(gbs, 1),
                          "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
-                         "traffic": None},
+                         "traffic": measured_traffic("decode_split")},
         }
         del Kp, Vp
 

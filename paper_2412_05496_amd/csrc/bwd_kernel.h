@@ -4,17 +4,18 @@
 //     dV = P^T dO,  dP = dO V^T,  dS' = P * (dP - delta),  delta = rowsum(dO * O),
 //     dS = dS' * d score_mod / d s,  dQ = scale * dS K,  dK = scale * dS^T Q.
 // Three kernels, no floating-point atomics (results are deterministic):
-//   bwd_delta_kernel   delta and LSE * log2(e) per query row.
+//   bwd_delta_kernel   -delta and the row constant of P = exp2(f(score) + rc) per query row.
 //   bwd_dkdv_kernel    one workgroup per 64 keys of one (b, hkv); walks the q-blocks listed for
 //                      that column of blocks (transposed BlockMask) for every query head of the
 //                      group; score tile in S = Q K^T orientation so that P and dS are the B
-//                      operands of dV^T += dO^T P and dK^T += Q^T dS.
+//                      operands of dV^T += dO^T P and dK^T += Q^T dS; the two waves that share
+//                      keys split the outputs (one dV, one dK) and exchange P / dS through LDS.
 //   bwd_dq_kernel      one workgroup per row of blocks of one (b, hq); walks the kv-blocks listed
 //                      for it; score tile transposed (S^T = K Q^T) so that dS^T is the B operand of
 //                      dQ^T += K^T dS^T and LSE / delta are per-lane scalars.
 // Tiles (Q, dO in the first kernel; K, V in the second) go from global memory straight into
-// XOR-swizzled LDS tiles, double buffered, one barrier per tile; the transposed operands
-// (dO^T, Q^T, K^T) come out of the same row-major tiles through transposing LDS reads.
+// XOR-swizzled LDS tiles, double buffered; the transposed operands (dO^T, Q^T, K^T) come out of
+// the same row-major tiles through transposing LDS reads.  dP accumulates on top of -delta.
 #pragma once
 
 #include <type_traits>

@@ -7,7 +7,8 @@
 // MFMA result layout every lane holds scores of ONE query (column l % 32) and 16 keys per 32-key
 // block in its registers: the row max / row sum of the online softmax are in-register reductions
 // plus one exchange between the two halves of the wave, and P^T is already laid out as the B
-// operand of O^T += V^T P^T.  K and V tiles go from global memory straight into LDS; K rows are
+// operand of O^T += V^T P^T.  K and V tiles go from global memory straight into LDS (LDS-DMA buffer
+// loads, issued one at a time between the MFMAs of the next score tile); K rows are
 // the A operand of K Q^T as they are, V^T fragments come out of the row-major V tile through the
 // transposing LDS read.  Q lives in registers for the whole kernel.
 //

@@ -7,7 +7,7 @@
 //                    (A/B operand of an MFMA whose contraction runs along D);
 //   transposing read ds_read_b64_tr_b16: 16 lanes cover a 4-row x 16-column block and lane i gets
 //                    column i of the 4 rows (operand of an MFMA whose contraction runs along rows).
-// Tiles are filled straight from global memory (global_load_lds_dwordx4): each wave instruction
+// Tiles are filled straight from global memory (buffer_load_dwordx4 ... lds): each wave instruction
 // deposits 64 x 16 bytes contiguously in LDS, so the permutation is applied on the global side --
 // lane L fetches the chunk that belongs at LDS position L.
 //
@@ -35,36 +35,6 @@ __device__ __forceinline__ constexpr int tile_off(int row, int chunk) {
 
 // vmcnt(0): every global load (including loads into LDS) this wave issued has completed.
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
-typedef __attribute__((address_space(3))) char lds_char;
-
-// Starts the copy of a 64 x D tile whose row 0 is at `g` (row stride `gs` elements) into `tile`.
-// All NW waves of the workgroup take part; completion needs wait_vmem() by every wave + a barrier.
-template <int D, int NW>
-struct TileLoader {
-    static constexpr int DC = D / 8;            // chunks per row
-    static constexpr int RPI = 64 / DC;         // rows per wave instruction (1 KiB)
-    static constexpr int NI = DC / NW;          // instructions per wave
-    static_assert(DC % NW == 0, "tile must split evenly over the waves");
-    int32_t off[NI];                            // per-lane element offset from the tile's first row
-    int wave;
-    __device__ __forceinline__ TileLoader(int64_t gs, int wave_, int lane) : wave(wave_) {
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int I = i * NW + wave;
-            const int row = I * RPI + lane / DC;
-            off[i] = (int32_t)(row * gs) + (((lane % DC) ^ swz<D>(row)) * 8);
-        }
-    }
-    __device__ __forceinline__ void start(bf16* tile, const bf16* g) const {
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int I = i * NW + wave;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + off[i]),
-                                             (__attribute__((address_space(3))) void*)(tile + I * 512), 16, 0, 0);
-        }
-    }
-};
 
 // Raw buffer resource (four scalar dwords) over `bytes` bytes at `p`: no stride, loads beyond
 // the end return zero instead of faulting.
