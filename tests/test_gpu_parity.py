@@ -32,6 +32,17 @@ SMALL = {
                                    score="identity", seed=14, prefix_len=200),
     "doc_causal_d128": wlm.Workload("doc", B=2, Hq=2, Hkv=1, S=1024, D=128, Bq=128, Bk=64, mask="doc_causal",
                                     score="identity", seed=15, doc_len_min=50, doc_len_max=400),
+    # the variants of the paper's 16k-token benchmark (section 6.2) at head dimension 64, 128 x 64 blocks
+    "noop_d64": wlm.Workload("noop128", B=1, Hq=2, Hkv=2, S=768, D=64, Bq=128, Bk=64, mask="none",
+                             score="identity", seed=16),
+    "causal_alibi_d64_gqa": wlm.Workload("alibi64", B=1, Hq=4, Hkv=1, S=1024, D=64, Bq=128, Bk=64, mask="causal",
+                                         score="alibi", seed=17),
+    "causal_softcap_d64": wlm.Workload("softcap64", B=1, Hq=2, Hkv=2, S=1024, D=64, Bq=128, Bk=64, mask="causal",
+                                       score="softcap", seed=18, softcap=30.0),
+    "prefix_lm_d64": wlm.Workload("prefix64", B=1, Hq=2, Hkv=1, S=1024, D=64, Bq=128, Bk=64, mask="prefix_lm",
+                                  score="identity", seed=19, prefix_len=300),
+    "softcap_unbounded_d128": wlm.Workload("softcap_big", B=1, Hq=2, Hkv=2, S=512, D=128, Bq=128, Bk=64, mask="causal",
+                                           score="softcap", seed=20, softcap=50.0),
 }
 
 
@@ -47,6 +58,30 @@ def test_forward_backward_small(name):
     O_ref, LSE_ref = fo.flex_attention(inp.Q, inp.K, inp.V, score, mask, inp.scale)
     check_output(O, LSE, O_ref, LSE_ref)
     dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids)
+    dQ_ref, dK_ref, dV_ref = fo.flex_attention_backward(inp.Q, inp.K, inp.V, inp.dO, score, mask, inp.scale)
+    check_grad("dQ", dQ, dQ_ref)
+    check_grad("dK", dK, dK_ref)
+    check_grad("dV", dV, dV_ref)
+
+
+def test_blockmask_without_full_blocks_gives_the_same_attention():
+    """Listing every FULL block as PARTIAL (mask_mod evaluated everywhere, paper section 4.2) must not change
+    the result beyond rounding: the tiles are merely visited in another order."""
+    import bench_sweep
+    import paper_2412_05496_amd as fa
+    wl = SMALL["cfg2_small"]
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    score, mask = oracle_mods(wl, inp)
+    O, LSE, bm, ids = run_forward(wl, inp, DEV)
+    mask_id, score_id, params, Q, K, V = ids
+    bm2 = bench_sweep.all_partial(fa, bm)
+    assert int(bm2.full_kv_num_blocks.sum()) == 0 and int(bm2.full_q_num_blocks.sum()) == 0
+    assert torch.equal(bm2.kv_num_blocks, bm.kv_num_blocks + bm.full_kv_num_blocks)
+    O2, LSE2 = torch.empty_like(O), torch.empty_like(LSE)
+    fa.flexattn_forward(Q, K, V, score_id, mask_id, params, bm2, inp.scale, O2, LSE2)
+    O_ref, LSE_ref = fo.flex_attention(inp.Q, inp.K, inp.V, score, mask, inp.scale)
+    check_output(O2, LSE2, O_ref, LSE_ref)
+    dQ, dK, dV = run_backward(wl, inp, DEV, O2, LSE2, bm2, ids)
     dQ_ref, dK_ref, dV_ref = fo.flex_attention_backward(inp.Q, inp.K, inp.V, inp.dO, score, mask, inp.scale)
     check_grad("dQ", dQ, dQ_ref)
     check_grad("dK", dK, dK_ref)
