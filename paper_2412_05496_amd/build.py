@@ -1,6 +1,8 @@
 """Builds libflexattn.so for gfx950 with hipcc (in-tree, no JIT cache).
 
-    python -m paper_2412_05496_amd.build [--jobs N] [--force]
+    python -m paper_2412_05496_amd.build [--jobs N] [--incremental]
+
+FLEXATTN_EXTRA_FLAGS (environment) is appended to the hipcc command line of every unit.
 
 Every (mask_mod, score_mod) variant of the forward and backward kernels is its own translation
 unit, so the compile runs in parallel.

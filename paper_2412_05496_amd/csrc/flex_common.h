@@ -137,7 +137,6 @@ struct ScoreMod {
     float k_bias;     // alibi_bias[h], pre-multiplied like k_acc
     float k_tab;      // factor applied to table entries
     float capl2;      // softcap * log2(e)
-    float inv_capl2;
     const float* tab; // rel_bias row of head h
     int rel_max;
 
@@ -149,7 +148,6 @@ struct ScoreMod {
         tab = kRel ? p.rel_bias + (int64_t)h * p.rel_len : nullptr;
         rel_max = kRel ? p.rel_len - 1 : 0;
         capl2 = kCap ? p.softcap * kLog2e : 0.0f;
-        inv_capl2 = kCap ? 1.0f / capl2 : 0.0f;
     }
 
     // Scaled score plus the additive biases, times the factor the following exp2 needs.
@@ -181,28 +179,9 @@ struct ScoreMod {
     // no rescaling, and p = exp2(-2 capl2 r) directly.
     __device__ __forceinline__ bool bounded() const { return kCap && 2.0f * capl2 <= 100.0f; }
 
-    __device__ __forceinline__ float dscore(float x) const {
-        if constexpr (kCap) {
-            float t = x * inv_capl2;      // tanh(s / cap)
-            return 1.0f - t * t;
-        } else {
-            return 1.0f;
-        }
-    }
-
-    // apply() plus the derivative d score_mod / d s up to the constant factor grad_scale():
-    // for the soft-cap, 1 - tanh^2 = 4 r (1 - r) with r from cap_r(), so g = r - r^2 and the 4 is
-    // folded into the final scaling of dQ / dK.
-    __device__ __forceinline__ float apply_with_grad(float acc, int dq, float& g) const {
-        if constexpr (kCap) {
-            const float r = cap_r(acc, dq);
-            g = __builtin_fmaf(-r, r, r);
-            return __builtin_fmaf(-2.0f * capl2, r, capl2);
-        } else {
-            g = 1.0f;
-            return pre(acc, dq);
-        }
-    }
+    // The backward needs d score_mod / d s up to the constant factor grad_scale(): for the soft-cap,
+    // 1 - tanh^2 = 4 r (1 - r) with r from cap_r(), so g = r - r^2 and the 4 is folded into the
+    // final scaling of dQ / dK (see p_with_grad).
     static constexpr float grad_scale() { return kCap ? 4.0f : 1.0f; }
 
     // Backward: P = exp(score' - LSE) from the raw dot product, with the row's constant folded in.

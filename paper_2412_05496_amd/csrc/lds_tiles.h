@@ -19,8 +19,6 @@
 
 namespace flexattn {
 
-constexpr int kTileRows = 64;
-
 // XOR applied to the chunk index (0 .. D/8-1) of row `row`.
 template <int D>
 __device__ __forceinline__ constexpr int swz(int row) {
