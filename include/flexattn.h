@@ -67,6 +67,7 @@ extern "C" {
 #define FLEXATTN_MASK_PREFIX_LM             FLEXATTN_MASK_OR(FLEXATTN_M_CAUSAL, FLEXATTN_M_PREFIX)
 #define FLEXATTN_MASK_SWA_CAUSAL_OR_PREFIX  FLEXATTN_MASK_OR(FLEXATTN_MASK_SWA_CAUSAL, FLEXATTN_M_PREFIX)
 #define FLEXATTN_MASK_CTX_LEN               FLEXATTN_M_CTX_LEN
+#define FLEXATTN_MASK_CTX_LEN_WINDOW        (FLEXATTN_M_CTX_LEN | FLEXATTN_M_SLIDING_WINDOW)
 
 /* ---- score_mod (section 3.1; nested score_mods, section 1.1) -------------------------
  * A bit set; the selected modifications are applied to the scaled score in this order:
@@ -227,7 +228,10 @@ int flexattn_paged_convert_blockmask(const int32_t* num_blocks, const int32_t* i
  *   ctx_lens   [nseq] int32: visible keys are kv_idx < ctx_lens[b] (0 is legal: O = 0,
  *              LSE = -inf).  score_mods see q_idx = ctx_lens[b] - 1 and the LOGICAL kv_idx.
  *   O [nseq, Hq, D] bf16 dense; LSE nullable [nseq, Hq] fp32.
- * page_size must be 16, 32, 64 or 128; Hq / Hkv <= 16; mask_id must be FLEXATTN_MASK_CTX_LEN.
+ * page_size must be 16, 32, 64 or 128; Hq / Hkv <= 16.  mask_id: FLEXATTN_MASK_CTX_LEN (which, with the query at
+ * q_idx = ctx_len - 1, is also the causal mask of a decode step: the offset conversion of section 5.2) or
+ * FLEXATTN_MASK_CTX_LEN_WINDOW (additionally q_idx - kv_idx <= params->window; splits wholly below the
+ * window are skipped).
  */
 typedef struct flexattn_decode_dims {
     int32_t nseq, Hq, Hkv, D, page_size, max_pages, n_pool_pages;

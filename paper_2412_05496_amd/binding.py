@@ -32,6 +32,7 @@ MASK_DOCUMENT_CAUSAL = M_DOCUMENT | M_CAUSAL
 MASK_PREFIX_LM = mask_or(M_CAUSAL, M_PREFIX)
 MASK_SWA_CAUSAL_OR_PREFIX = mask_or(MASK_SWA_CAUSAL, M_PREFIX)
 MASK_CTX_LEN = M_CTX_LEN
+MASK_CTX_LEN_WINDOW = M_CTX_LEN | M_SLIDING_WINDOW
 
 SCORE_IDENTITY, SCORE_ALIBI, SCORE_REL_BIAS, SCORE_SOFTCAP = 0, 1, 2, 4
 

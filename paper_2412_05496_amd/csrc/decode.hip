@@ -28,6 +28,7 @@ struct DecodeArgs {
     int64_t pt_stride;
     const int32_t* ctx_lens;
     int nseq, Hq, Hkv, G, page_size, page_shift, max_splits;
+    int window;          // sliding window (q_idx - kv <= window), -1 if none
     float scale;
     flexattn_mod_params p;
     float* part_O;    // [nseq, Hq, max_splits, D]
@@ -48,9 +49,13 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
     const int b = blockIdx.x / a.Hkv, hkv = blockIdx.x % a.Hkv;
     const int split = blockIdx.y * kDecWaves + wave;
     const int ctx = a.ctx_lens[b];
+    // The query sits at q_idx = ctx - 1 (the offset of the decode step), so "causal" is kv < ctx and a
+    // sliding window adds the lower bound kv >= q_idx - window.
+    const int kv_lo = a.window >= 0 ? max(ctx - 1 - a.window, 0) : 0;
     const int tok_begin = split * kDecSplit;
-    if (tok_begin >= ctx) return;                       // wave-uniform; the kernel has no barriers
+    if (tok_begin >= ctx || tok_begin + kDecSplit <= kv_lo) return;   // wave-uniform; the kernel has no barriers
     const int tok_end = min(ctx, tok_begin + kDecSplit);
+    const int tok_first = max(tok_begin, kv_lo & ~(kDecTile - 1));    // first tile that holds a visible key
     bf16* k_tile = smem + wave * 2 * TILE;
     bf16* v_tile = k_tile + TILE;
 
@@ -82,7 +87,7 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
 
-    for (int tok0 = tok_begin; tok0 < tok_end; tok0 += kDecTile) {
+    for (int tok0 = tok_first; tok0 < tok_end; tok0 += kDecTile) {
         // ---- gather 32 K rows and 32 V rows through the page table, straight into LDS
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -105,14 +110,15 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(k_reader.read(0, 0, ks), qf[ks], sacc);
 
-        // ---- score_mod, mask kv < ctx_len (only the last tile can hold masked keys), softmax
-        const bool ragged = tok0 + kDecTile > tok_end;
+        // ---- score_mod, mask kv_lo <= kv < ctx_len (only the first and the last tile can hold masked
+        // keys), softmax
+        const bool ragged = tok0 + kDecTile > tok_end || tok0 < kv_lo;
         float mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int kv = tok0 + crow(r, half);
             float x = smod.apply(sacc[r], q_idx - kv);
-            if (ragged && kv >= tok_end) x = -INFINITY;
+            if (ragged && (kv >= tok_end || kv < kv_lo)) x = -INFINITY;
             sacc[r] = x;
             mx = fmaxf(mx, x);
         }
@@ -174,6 +180,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
     const int b = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq;
     const int ctx = a.ctx_lens[b];
     const int ns = (ctx + kDecSplit - 1) / kDecSplit;
+    const int s0 = a.window >= 0 ? max(ctx - 1 - a.window, 0) / kDecSplit : 0;     // splits below the window are empty
     const int64_t base = ((int64_t)b * a.Hq + hq) * a.max_splits;
     bf16* o = a.O + ((int64_t)b * a.Hq + hq) * D;
     constexpr int PER = D / 64;
@@ -184,11 +191,11 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
         return;
     }
     float m = -INFINITY;
-    for (int s = 0; s < ns; ++s) m = fmaxf(m, a.part_ml[(base + s) * 2]);
+    for (int s = s0; s < ns; ++s) m = fmaxf(m, a.part_ml[(base + s) * 2]);
     float L = 0.0f, acc[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) acc[i] = 0.0f;
-    for (int s = 0; s < ns; ++s) {
+    for (int s = s0; s < ns; ++s) {
         const float wgt = fast_exp2(a.part_ml[(base + s) * 2] - m);
         L += wgt * a.part_ml[(base + s) * 2 + 1];
         const float* po = a.part_O + (base + s) * D + lane * PER;
@@ -260,7 +267,8 @@ extern "C" int flexattn_paged_decode(const flexattn_decode_dims* d, const void* 
     if (((uintptr_t)Q & 15) || ((uintptr_t)K_pool & 15) || ((uintptr_t)V_pool & 15) || ((uintptr_t)ws & 15))
         return FLEXATTN_ERR_INVALID_ARG;
     if (!(scale > 0.0f)) return FLEXATTN_ERR_INVALID_ARG;
-    if (mask_id != FLEXATTN_MASK_CTX_LEN) return FLEXATTN_ERR_UNSUPPORTED;
+    const uint32_t kCtxWindow = FLEXATTN_M_CTX_LEN | FLEXATTN_M_SLIDING_WINDOW;   // one AND-term
+    if (mask_id != FLEXATTN_MASK_CTX_LEN && mask_id != kCtxWindow) return FLEXATTN_ERR_UNSUPPORTED;
     flexattn_mod_params p = {};
     if (params) p = *params;
     p.ctx_lens = ctx_lens;
@@ -275,6 +283,7 @@ extern "C" int flexattn_paged_decode(const flexattn_decode_dims* d, const void* 
     a.page_size = d->page_size;
     a.page_shift = __builtin_ctz((unsigned)d->page_size);
     a.max_splits = max_splits_of(d);
+    a.window = mask_id == kCtxWindow ? p.window : -1;
     a.scale = scale; a.p = p;
     const size_t items = (size_t)d->nseq * d->Hq * a.max_splits;
     a.part_O = (float*)ws;

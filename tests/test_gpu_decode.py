@@ -12,20 +12,22 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def run_decode(inp, score_id=0, params=None):
+def run_decode(inp, score_id=0, params=None, mask_id=None):
     import paper_2412_05496_amd as fa
     params = params or fa.ModParams()
+    mask_id = fa.MASK_CTX_LEN if mask_id is None else mask_id
     Q = inp.Q.to(DEV)
     O = torch.full((Q.shape[0], Q.shape[1], Q.shape[3]), float("nan"), dtype=torch.bfloat16, device=DEV)
     LSE = torch.full((Q.shape[0], Q.shape[1]), float("nan"), dtype=torch.float32, device=DEV)
     fa.flexattn_paged_decode(Q, inp.K_pool.to(DEV), inp.V_pool.to(DEV), inp.page_table.to(DEV),
-                             inp.ctx_lens.to(DEV), score_id, fa.MASK_CTX_LEN, params, inp.scale, O, LSE)
+                             inp.ctx_lens.to(DEV), score_id, mask_id, params, inp.scale, O, LSE)
     torch.cuda.synchronize()
     return O, LSE
 
 
-def compare(inp, O, LSE, score_mod):
-    O_ref, LSE_ref = fo.paged_decode(inp.Q, inp.K_pool, inp.V_pool, inp.page_table, inp.ctx_lens, score_mod, inp.scale)
+def compare(inp, O, LSE, score_mod, mask_mod=None):
+    O_ref, LSE_ref = fo.paged_decode(inp.Q, inp.K_pool, inp.V_pool, inp.page_table, inp.ctx_lens, score_mod, inp.scale,
+                                     mask_mod)
     check_output(O[:, :, None, :], LSE[:, :, None], O_ref, LSE_ref)
 
 
@@ -48,6 +50,24 @@ def test_shapes_and_page_sizes(D, G, page):
     print(f"[case] D={D} G={G} page={page} ctx={inp.ctx_lens.tolist()}", flush=True)
     O, LSE = run_decode(inp)
     compare(inp, O, LSE, fo.Identity())
+
+
+@pytest.mark.parametrize("window", [0, 5, 31, 32, 100, 511, 512, 1300, 5000])
+def test_sliding_window_in_decode(window):
+    """Decode with a q-dependent mask: the query sits at q_idx = ctx_len - 1, so the window keeps
+    kv >= ctx_len - 1 - window; splits wholly below it are skipped by the kernel."""
+    import paper_2412_05496_amd as fa
+    ctx = [1, 17, 64, 511, 512, 513, 1024, 1500, 2047, 2600, 700, 33]
+    wl = wlm.CFG5.scaled(B=len(ctx), Hq=8, Hkv=2, max_pages=192)
+    inp = wlm.make_decode_inputs(wl, ctx_lens=ctx, slack_pages=5)
+    print(f"[case] window={window} ctx={ctx}", flush=True)
+    O, LSE = run_decode(inp, fa.SCORE_IDENTITY, fa.ModParams(window=window), fa.MASK_CTX_LEN_WINDOW)
+    mask = fo.and_mask(fo.ctx_len_mask(inp.ctx_lens), fo.sliding_window_mask(window))
+    compare(inp, O, LSE, fo.Identity(), mask)
+    slopes = wlm.alibi_slopes(8)
+    O, LSE = run_decode(inp, fa.SCORE_ALIBI, fa.ModParams(window=window, alibi_bias=(-slopes).to(DEV)),
+                        fa.MASK_CTX_LEN_WINDOW)
+    compare(inp, O, LSE, fo.Alibi(-slopes.double()), mask)
 
 
 def test_score_mods_in_decode():
