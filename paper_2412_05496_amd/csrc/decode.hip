@@ -5,7 +5,8 @@
 // KV split) and never synchronises with another: it walks its logical pages 32 keys at a time,
 // looks each key's page up in the page table and pulls the K and V rows straight from the pool into
 // its private, XOR-swizzled LDS tiles (global_load_lds_dwordx4: every wave instruction moves 1 KiB
-// of whole 256-byte rows, so the page gather is fully coalesced).  S^T = K Q^T takes K rows from
+// of whole 256-byte rows, so the page gather is fully coalesced); the gather of the next tile is
+// started as soon as the current tile's operand fragments sit in registers.  S^T = K Q^T takes K rows from
 // LDS as the A operand with the G query heads of the group as (zero-padded) columns of the B
 // operand, so K and V are read once per KV head, never once per query head; V^T comes out of the
 // row-major V tile through the transposing LDS read.  Each wave leaves (m, l, O) of its split in
@@ -87,28 +88,58 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
 
-    for (int tok0 = tok_first; tok0 < tok_end; tok0 += kDecTile) {
-        // ---- gather 32 K rows and 32 V rows through the page table, straight into LDS
+    // Page ids of the rows this lane fetches for one tile (NI wave instructions, RPI rows each; rows
+    // past the context re-read the last key).
+    auto lookup = [&](int tok0, int (&pg)[NI]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int tok = min(tok0 + i * RPI + lane / DC, ctx - 1);
+            pg[i] = pt[tok >> a.page_shift];
+        }
+    };
+    // Gather of the 32 K rows and 32 V rows of a tile through the page table, straight into LDS.  The
+    // LDS-DMA loads are inline assembly so that the compiler does not make later LDS reads wait for
+    // them (see lds_tiles.h); completion is awaited with wait_vmem() at the top of the next iteration.
+    auto gather = [&](int tok0, const int (&pg)[NI]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int row = i * RPI + lane / DC;
-            const int tok = min(tok0 + row, ctx - 1);                 // rows past the context re-read the last key
-            const int pg = pt[tok >> a.page_shift];
-            const int64_t off = ((int64_t)pg * a.Hkv + hkv) * slab + (int64_t)(tok & page_mask) * D +
+            const int tok = min(tok0 + row, ctx - 1);
+            const int64_t off = ((int64_t)pg[i] * a.Hkv + hkv) * slab + (int64_t)(tok & page_mask) * D +
                                 (((lane % DC) ^ swz<D>(row)) * 8);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.K_pool + off),
-                                             (__attribute__((address_space(3))) void*)(k_tile + i * 512), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.V_pool + off),
-                                             (__attribute__((address_space(3))) void*)(v_tile + i * 512), 16, 0, 0);
+            dma_global(lds_addr(k_tile + i * 512), a.K_pool + off);
+            dma_global(lds_addr(v_tile + i * 512), a.V_pool + off);
         }
+    };
+
+    int pg_next[NI];
+    lookup(tok_first, pg_next);
+    gather(tok_first, pg_next);
+    if (tok_first + kDecTile < tok_end) lookup(tok_first + kDecTile, pg_next);
+
+    for (int tok0 = tok_first; tok0 < tok_end; tok0 += kDecTile) {
+        // ---- tile tok0 has landed; take every operand fragment out of LDS, then start the gather of
+        // the next tile into the same (wave-private) buffers so that it runs beside this tile's compute
         wait_vmem();
+        bf16x8 kfr[D / 16], vfr[D / 32][2];
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) kfr[ks] = k_reader.read(0, 0, ks);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) vfr[db][c] = v_reader.read(0, 16 * c, db);
+        if (tok0 + kDecTile < tok_end) {
+            __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): the fragments are in registers
+            gather(tok0 + kDecTile, pg_next);
+            if (tok0 + 2 * kDecTile < tok_end) lookup(tok0 + 2 * kDecTile, pg_next);
+        }
 
         // ---- S^T = K Q^T
         f32x16 sacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(k_reader.read(0, 0, ks), qf[ks], sacc);
+        for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(kfr[ks], qf[ks], sacc);
 
         // ---- score_mod, mask kv_lo <= kv < ctx_len (only the first and the last tile can hold masked
         // keys), softmax
@@ -152,7 +183,7 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int c = 0; c < 2; ++c) oacc[db] = mfma32(v_reader.read(0, 16 * c, db), pf[c], oacc[db]);
+            for (int c = 0; c < 2; ++c) oacc[db] = mfma32(vfr[db][c], pf[c], oacc[db]);
     }
 
     const float l_tot = l_run + swap_halves(l_run);

@@ -85,6 +85,12 @@ __device__ __forceinline__ void dma_x2(i32x4 rsrc, uint32_t lds, int v0, int v1,
                  :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(v0), "v"(v1), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
+// 64 lanes x 16 bytes from per-lane global addresses to `lds` .. +1024.
+__device__ __forceinline__ void dma_global(uint32_t lds, const void* gptr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(gptr) : "memory");
+}
+
 __device__ __forceinline__ void dma_x1(i32x4 rsrc, uint32_t lds, int v0, int soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(v0), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
