@@ -16,9 +16,9 @@
 
 namespace flexattn {
 
-constexpr int kDecWaves = 4;       // waves (= splits) per workgroup
+constexpr int kDecWaves = 4;       // waves per workgroup (the mapping below assumes 4)
 constexpr int kDecTile = 32;       // keys per inner tile
-constexpr int kDecSplit = 512;     // keys per split
+constexpr int kDecSplit = 1024;    // keys per split
 
 struct DecodeArgs {
     const bf16* Q;
@@ -47,8 +47,16 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
     __shared__ __attribute__((aligned(1024))) bf16 smem[kDecWaves * 2 * TILE];   // per wave: K tile, V tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
-    const int b = blockIdx.x / a.Hkv, hkv = blockIdx.x % a.Hkv;
-    const int split = blockIdx.y * kDecWaves + wave;
+    // workgroup -> consecutive splits of one (sequence, KV head): blockIdx.x walks the (sequence, KV
+    // head) units, blockIdx.y the groups of splits, so the splits of a long sequence are spread over the
+    // launch.  When a sequence has fewer splits than a workgroup has waves, the spare waves take the
+    // following units instead of idling.
+    const int spw = a.max_splits >= 4 ? 4 : (a.max_splits >= 2 ? 2 : 1);   // splits per workgroup
+    const int upw = kDecWaves / spw;                     // units per workgroup
+    const int split = blockIdx.y * spw + wave % spw;
+    const int unit = blockIdx.x * upw + wave / spw;
+    if (unit >= a.nseq * a.Hkv || split >= a.max_splits) return;
+    const int b = unit / a.Hkv, hkv = unit % a.Hkv;
     const int ctx = a.ctx_lens[b];
     // The query sits at q_idx = ctx - 1 (the offset of the decode step), so "causal" is kv < ctx and a
     // sliding window adds the lower bound kv >= q_idx - window.
@@ -188,8 +196,8 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
 
     const float l_tot = l_run + swap_halves(l_run);
     if (g_ok) {
-        const int64_t item = ((int64_t)b * a.Hq + hq) * a.max_splits + split;
-        float* po = a.part_O + item * D;
+        const int64_t out_item = ((int64_t)b * a.Hq + hq) * a.max_splits + split;
+        float* po = a.part_O + out_item * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -198,8 +206,8 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
                 *(f32x4*)(po + db * 32 + 8 * rg + 4 * half) = v;
             }
         if (half == 0) {
-            a.part_ml[item * 2] = m_run;
-            a.part_ml[item * 2 + 1] = l_tot;
+            a.part_ml[out_item * 2] = m_run;
+            a.part_ml[out_item * 2 + 1] = l_tot;
         }
     }
 }
@@ -246,7 +254,8 @@ static int max_splits_of(const flexattn_decode_dims* d) {
 
 template <int D>
 static int launch_decode(const DecodeArgs& a, uint32_t score_id, hipStream_t st) {
-    const dim3 grid((unsigned)(a.nseq * a.Hkv), (unsigned)((a.max_splits + kDecWaves - 1) / kDecWaves));
+    const int spw = a.max_splits >= 4 ? 4 : (a.max_splits >= 2 ? 2 : 1), upw = kDecWaves / spw;
+    const dim3 grid((unsigned)((a.nseq * a.Hkv + upw - 1) / upw), (unsigned)((a.max_splits + spw - 1) / spw));
     switch (score_id) {
 #define CASE(S)                                                                                           \
     case S:                                                                                               \
