@@ -187,3 +187,26 @@ def make_decode_inputs(wl: Workload, ctx_lens: Optional[list[int]] = None,
     V_pool = randn_bf16(gen, n_pool, wl.Hkv, P, wl.D)
     return DecodeInputs(wl, Q, K_pool, V_pool, page_table.contiguous(),
                         ctx.to(torch.int32).contiguous(), 1.0 / math.sqrt(wl.D))
+
+
+@dataclass
+class PrefillInputs:
+    wl: Workload
+    Q: torch.Tensor            # [nseq, Hq, q_len, D] bf16: the chunk's queries
+    K_pool: torch.Tensor
+    V_pool: torch.Tensor
+    page_table: torch.Tensor
+    kv_lens: torch.Tensor      # [nseq] int32: tokens in the cache, the chunk's own included
+    q_offsets: torch.Tensor    # [nseq] int32: position of the chunk's first query = kv_lens - q_len
+    scale: float
+
+
+def make_prefill_inputs(wl: Workload, kv_lens: list[int], q_len: int, slack_pages: int = 0) -> PrefillInputs:
+    """A chunk of q_len new tokens per sequence on top of a paged cache (chunked prefill): the cache
+    already holds the chunk's own keys, so sequence b has kv_lens[b] >= q_len tokens."""
+    assert all(n >= q_len for n in kv_lens)
+    d = make_decode_inputs(wl, ctx_lens=kv_lens, slack_pages=slack_pages)
+    gen = _gen(wl.seed + 7919)
+    Q = randn_bf16(gen, wl.B, wl.Hq, q_len, wl.D)
+    return PrefillInputs(wl, Q, d.K_pool, d.V_pool, d.page_table, d.ctx_lens,
+                         (d.ctx_lens - q_len).to(torch.int32).contiguous(), d.scale)

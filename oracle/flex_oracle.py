@@ -23,6 +23,11 @@ What follows what (paper = arXiv 2412.05496):
 * ``paged_decode``              section 5.1: the physical cache is addressed through
                                 the page table; the result must equal attention
                                 over the logical (un-paged) cache.
+* ``with_q_offset`` / ``QOffset``  section 5.2: at inference the mods are called with q_idx + offset,
+                                the number of tokens already processed.
+* ``paged_attention``           sections 5.1 + 5.2 for a chunk of several query tokens per sequence
+                                (chunked prefill): un-page, then Eq. 1 with the mods shifted
+                                by each sequence's offset.
 * ``flex_attention_backward``   the paper only states that a backward template
                                 exists (section 4.1); this is ordinary calculus on
                                 Eq. 1, pinned by finite differences in the tests.
@@ -416,4 +421,54 @@ def paged_decode(Q, K_pool, V_pool, page_table, ctx_lens, score_mod: ScoreMod, s
             Pm, lse = _softmax_rows(s_mod, keep)
             O[b, h] = Pm @ Vl[h // G].to(F64)
             LSE[b, h] = lse
+    return O, LSE
+
+
+# --------------------------------------------------------------------------
+# Offset conversion (section 5.2) and paged attention with several query tokens
+# --------------------------------------------------------------------------
+def with_q_offset(mask_mod: MaskMod, q_offsets: torch.Tensor) -> MaskMod:
+    """The inference counterpart of a mask_mod: it sees q_idx + q_offsets[b]."""
+    off = q_offsets.to(torch.int64)
+
+    def mod(b, h, q_idx, kv_idx):
+        return mask_mod(b, h, q_idx + off[b], kv_idx)
+    return mod
+
+
+class QOffset(ScoreMod):
+    """The inference counterpart of a score_mod: it sees q_idx + q_offsets[b]."""
+
+    def __init__(self, inner: ScoreMod, q_offsets: torch.Tensor):
+        self.inner, self.off = inner, q_offsets.to(torch.int64)
+
+    def __call__(self, score, b, h, q_idx, kv_idx):
+        return self.inner(score, b, h, q_idx + self.off[b], kv_idx)
+
+    def grad(self, score, b, h, q_idx, kv_idx):
+        return self.inner.grad(score, b, h, q_idx + self.off[b], kv_idx)
+
+
+def paged_attention(Q, K_pool, V_pool, page_table, kv_lens, q_offsets, score_mod: ScoreMod, mask_mod: MaskMod,
+                    scale: Optional[float] = None):
+    """Q [nseq,Hq,Lq,D] (query i of sequence b sits at position q_offsets[b] + i); pools
+    [n_pages,Hkv,P,D]; page_table [nseq,max_pages]; kv_lens [nseq] tokens held by the cache of each
+    sequence.  `score_mod` / `mask_mod` are the user's (training-time) mods: they are shifted here.
+    Keys run over whole pages; as in paged_decode the mask, not the slicing, hides what lies past
+    kv_lens[b].  Returns O [nseq,Hq,Lq,D], LSE [nseq,Hq,Lq] (fp64)."""
+    nseq, Hq, Lq, D = Q.shape
+    Hkv, P = K_pool.shape[1], K_pool.shape[2]
+    G = Hq // Hkv
+    scale = 1.0 / math.sqrt(D) if scale is None else scale
+    score_inf, mask_inf = QOffset(score_mod, q_offsets), with_q_offset(mask_mod, q_offsets)
+    O = torch.zeros(nseq, Hq, Lq, D, dtype=F64)
+    LSE = torch.full((nseq, Hq, Lq), NEG_INF, dtype=F64)
+    for b in range(nseq):
+        n_padded = ((int(kv_lens[b]) + P - 1) // P) * P
+        if n_padded == 0:
+            continue
+        Kl = unpage(K_pool, page_table[b], n_padded)
+        Vl = unpage(V_pool, page_table[b], n_padded)
+        for h in range(Hq):
+            O[b, h], LSE[b, h] = attention_head(Q[b, h], Kl[h // G], Vl[h // G], score_inf, mask_inf, scale, b, h)
     return O, LSE
