@@ -91,6 +91,10 @@ typedef struct flexattn_mod_params {
     const float*   alibi_bias;    /* ALIBI: [Hq] fp32                                          */
     const float*   rel_bias;      /* REL_BIAS: [Hq, rel_len] fp32, row-major                   */
     const int32_t* ctx_lens;      /* CTX_LEN: [B] int32                                        */
+    const int32_t* q_offsets;     /* nullable [B] int32: every mod sees q_idx + q_offsets[b], the
+                                     offset conversion for inference of section 5.2 (number of
+                                     tokens of sequence b processed before this call's first
+                                     query); BlockMask build, forward and backward honour it    */
 } flexattn_mod_params;
 
 /* A 4-D tensor [batch, head, seq, D] with unit stride in D.  ptr is 16-byte aligned, the
@@ -218,6 +222,30 @@ int flexattn_paged_convert_blockmask(const int32_t* num_blocks, const int32_t* i
                                      const int32_t* page_table, int64_t pt_stride,
                                      int32_t* phys_indices, int32_t* phys2log, int32_t n_pool_pages,
                                      void* stream);
+
+/* Paged forward: a chunk of q_len query tokens per sequence against a paged KV cache (chunked
+ * prefill: fused indirect access of section 5.1 with the offset conversion of section 5.2).
+ * The computation is that of flexattn_forward over the LOGICAL BlockMask `bm`, which must have
+ * Bm == B (every sequence has its own pages) and Bk == page_size, and is normally built with
+ * params->q_offsets[b] = number of tokens of sequence b that precede the chunk.  K and V rows
+ * come from the pools: the page of the j-th entry of a list of `bm` is the j-th entry of the
+ * converted list (phys_kv_indices beside bm->kv_indices, phys_full_kv_indices beside
+ * bm->full_kv_indices; same shapes, made by flexattn_paged_convert_blockmask), so the kernel
+ * never looks the page table up and the mods keep seeing the logical kv_idx.  Pages are whole
+ * blocks: keys past the end of a sequence inside its last page must be hidden by the mask (a
+ * causal mask with q_offsets does so).
+ *   dims->kv_len    logical KV length `bm` was built for (a multiple of page_size)
+ *   K_pool, V_pool  [n_pool_pages, Hkv, page_size, D] bf16, dense; page_size is 64 or 128
+ *   converted entries are clamped to [0, n_pool_pages): a wrong entry reads the wrong page, never
+ *   outside the pools.
+ * O, LSE as in flexattn_forward.
+ */
+int flexattn_paged_forward(const flexattn_dims* dims, const flexattn_tensor* Q,
+                           const void* K_pool, const void* V_pool, int32_t page_size, int32_t n_pool_pages,
+                           uint32_t score_id, uint32_t mask_id, const flexattn_mod_params* params,
+                           const flexattn_blockmask* bm, const int32_t* phys_kv_indices,
+                           const int32_t* phys_full_kv_indices, float scale,
+                           const flexattn_tensor* O, float* LSE, void* stream);
 
 /* Paged decode: one query token per sequence against a paged KV cache (decoding template of
  * section 4.1 + fused indirect access of section 5.1), split over KV and combined.

@@ -51,7 +51,7 @@ class FlexAttnError(RuntimeError):
 class _ModParams(C.Structure):
     _fields_ = [("window", C.c_int32), ("prefix_len", C.c_int32), ("softcap", C.c_float), ("rel_len", C.c_int32),
                 ("doc_ids", C.c_void_p), ("doc_stride_b", C.c_int64), ("alibi_bias", C.c_void_p),
-                ("rel_bias", C.c_void_p), ("ctx_lens", C.c_void_p)]
+                ("rel_bias", C.c_void_p), ("ctx_lens", C.c_void_p), ("q_offsets", C.c_void_p)]
 
 
 class _Tensor(C.Structure):
@@ -104,6 +104,10 @@ def _lib():
     lib.flexattn_forward.restype = C.c_int
     lib.flexattn_forward.argtypes = [P(_Dims), P(_Tensor), P(_Tensor), P(_Tensor), C.c_uint32, C.c_uint32,
                                      P(_ModParams), P(_BlockMask), C.c_float, P(_Tensor), C.c_void_p, C.c_void_p]
+    lib.flexattn_paged_forward.restype = C.c_int
+    lib.flexattn_paged_forward.argtypes = [P(_Dims), P(_Tensor), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                           C.c_uint32, C.c_uint32, P(_ModParams), P(_BlockMask), C.c_void_p,
+                                           C.c_void_p, C.c_float, P(_Tensor), C.c_void_p, C.c_void_p]
     lib.flexattn_backward_workspace_bytes.restype = C.c_size_t
     lib.flexattn_backward_workspace_bytes.argtypes = [P(_Dims)]
     lib.flexattn_backward.restype = C.c_int
@@ -154,6 +158,7 @@ class ModParams:
     alibi_bias: Optional[torch.Tensor] = None    # fp32 [Hq]
     rel_bias: Optional[torch.Tensor] = None      # fp32 [Hq, rel_len]
     ctx_lens: Optional[torch.Tensor] = None      # int32 [B]
+    q_offsets: Optional[torch.Tensor] = None     # int32 [B]: the mods see q_idx + q_offsets[b]
 
     def _c(self) -> _ModParams:
         p = _ModParams()
@@ -172,6 +177,9 @@ class ModParams:
         if self.ctx_lens is not None:
             assert self.ctx_lens.dtype == torch.int32 and self.ctx_lens.is_cuda and self.ctx_lens.is_contiguous()
             p.ctx_lens = self.ctx_lens.data_ptr()
+        if self.q_offsets is not None:
+            assert self.q_offsets.dtype == torch.int32 and self.q_offsets.is_cuda and self.q_offsets.is_contiguous()
+            p.q_offsets = self.q_offsets.data_ptr()
         return p
 
 
@@ -249,6 +257,26 @@ def flexattn_forward(Q, K, V, score_id: int, mask_id: int, params: ModParams, bm
     _check(_lib().flexattn_forward(C.byref(d), C.byref(tq), C.byref(tk), C.byref(tv), score_id, mask_id,
                                    C.byref(p), C.byref(c), scale, C.byref(to), LSE.data_ptr(), _stream()),
            "flexattn_forward")
+    return O, LSE
+
+
+def flexattn_paged_forward(Q, K_pool, V_pool, score_id: int, mask_id: int, params: ModParams, bm: BlockMask,
+                           phys_kv_indices: torch.Tensor, phys_full_kv_indices: torch.Tensor, scale: float,
+                           O: torch.Tensor, LSE: torch.Tensor):
+    """Q [nseq, Hq, q_len, D]; pools [n_pages, Hkv, page, D] contiguous; `bm` is the logical BlockMask
+    (Bm == nseq, Bk == page), the phys_* tensors its converted kv lists."""
+    assert K_pool.is_contiguous() and V_pool.is_contiguous() and K_pool.shape == V_pool.shape
+    assert LSE.dtype == torch.float32 and LSE.is_contiguous() and LSE.shape == Q.shape[:3]
+    for phys, logical in ((phys_kv_indices, bm.kv_indices), (phys_full_kv_indices, bm.full_kv_indices)):
+        assert phys.dtype == torch.int32 and phys.is_contiguous() and phys.shape == logical.shape
+    n_pool, Hkv, page, D = K_pool.shape
+    d = _Dims(Q.shape[0], Q.shape[1], Hkv, Q.shape[2], bm.kv_len, D)
+    p, c, tq, to = params._c(), bm._c(), _tensor(Q), _tensor(O)
+    _check(_lib().flexattn_paged_forward(C.byref(d), C.byref(tq), K_pool.data_ptr(), V_pool.data_ptr(), page, n_pool,
+                                         score_id, mask_id, C.byref(p), C.byref(c), phys_kv_indices.data_ptr(),
+                                         phys_full_kv_indices.data_ptr(), scale, C.byref(to), LSE.data_ptr(),
+                                         _stream()),
+           "flexattn_paged_forward")
     return O, LSE
 
 

@@ -36,6 +36,7 @@ def _units():
     for i in range(NUM_VARIANTS):
         units.append((f"fwd_inst_{i}", "fwd_inst.hip", [f"-DFLEXATTN_VARIANT={i}"]))
         units.append((f"bwd_inst_{i}", "bwd_inst.hip", [f"-DFLEXATTN_VARIANT={i}"]))
+        units.append((f"fwd_paged_inst_{i}", "fwd_paged_inst.hip", [f"-DFLEXATTN_VARIANT={i}"]))
     return [u for u in units if os.path.exists(os.path.join(CSRC, u[1]))]
 
 

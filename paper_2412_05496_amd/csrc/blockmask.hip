@@ -25,9 +25,10 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void classify_blocks_kernel(
         const int h = (int)((blk / ((long long)NC * NR)) % Hm);
         const int b = (int)(blk / ((long long)NC * NR * Hm));
         const int n = Bq * Bk;
+        const int q_off = q_offset_of(p, b);
         int cnt = 0;
         for (int e = lane; e < n; e += 64) {
-            const int q = i * Bq + e / Bk, kv = j * Bk + e % Bk;
+            const int q = q_off + i * Bq + e / Bk, kv = j * Bk + e % Bk;
             MaskRow<MASK> row(p, b, h, q);
             cnt += row(kv) ? 1 : 0;
         }

@@ -162,6 +162,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
     const TrReader<D> tr_own(lane, out_tile + x * 32 * D * 2), tr_other(lane, out_tile + (1 - x) * 32 * D * 2);
     const uint32_t row_lds = lds_addr(&s_row[0][0][0]) + (32 * x + 4 * half) * 4;
     const uint32_t xchg_mine = lds_addr(&s_xchg[w][0][lane]), xchg_theirs = lds_addr(&s_xchg[w ^ 2][0][lane]);
+    const int q_off = q_offset_of(a.p, b);
 
     for (int g = 0; g < a.G; ++g) {
         const int hq = hkv * a.G + g;
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                 constexpr std::integral_constant<int, SLOT ^ 1> ld_slot{};
                 load_begin(ld_slot);
                 const bool partial = part_of[SLOT];
-                const int q_first = q0_of[SLOT] + 32 * x;
+                const int q_first = q_off + q0_of[SLOT] + 32 * x;   // as the mods see it
 
                 // scores
                 f32x4 nd[4], rcv4[4];
@@ -417,9 +418,10 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     const i32x4 v_rsrc = make_rsrc(a.V + b * a.v_sb + hkv * a.v_sh, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
     const int k_row_bytes = (int)a.k_ss * 2, v_row_bytes = (int)a.v_ss * 2;
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
-    const MaskRow<MASK> mrow(a.p, b, hq, q_row);
+    const int q_pos = q_row + q_offset_of(a.p, b);   // as the mods see it
+    const MaskRow<MASK> mrow(a.p, b, hq, q_pos);
 
-    TileWalk walk(a.full_kv_idx + line * a.NC, a.kv_idx + line * a.NC, n_full, n_part, sub, a.Bk);
+    TileWalk<> walk(a.full_kv_idx + line * a.NC, a.kv_idx + line * a.NC, n_full, n_part, sub, a.Bk);
     const WaveTileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
     auto load_tiles = [&](int buf, int kv0) {
         k_loader.start(k_rsrc, lds_addr(smem) + buf * (TILE * 2), kv0 * k_row_bytes);
@@ -497,7 +499,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
             for (int r = 0; r < 16; ++r) {
                 const int kv = kv0_cur + kvb * 32 + crow(r, half);
                 float gr;
-                const float pe = smod.p_with_grad(sacc[r], q_row - kv, rc, gr);
+                const float pe = smod.p_with_grad(sacc[r], q_pos - kv, rc, gr);
                 dpacc[r] = pe * gr * dpacc[r];
             }
             if (partial) {

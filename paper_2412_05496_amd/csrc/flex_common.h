@@ -103,6 +103,12 @@ struct MaskTermRow {
     }
 };
 
+// Offset conversion for inference (section 5.2): the position the mods see for query row 0 of
+// batch entry b.
+__device__ __forceinline__ int q_offset_of(const flexattn_mod_params& p, int b) {
+    return p.q_offsets ? ldc(p.q_offsets + b) : 0;
+}
+
 template <uint32_t MASK>
 struct MaskRow {
     static constexpr uint32_t T0 = MASK & 0xffu, T1 = (MASK >> 8) & 0xffu;

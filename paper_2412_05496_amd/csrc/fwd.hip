@@ -11,6 +11,12 @@ typedef int (*FwdLauncher)(const FwdArgs&, int, int, hipStream_t);
 static const FwdLauncher kFwdLaunchers[kNumVariants] = {fwd_launch_0, fwd_launch_1, fwd_launch_2,
                                                         fwd_launch_3, fwd_launch_4, fwd_launch_5,
                                                         fwd_launch_6, fwd_launch_7, fwd_launch_8};
+#define DECL(i) int fwd_paged_launch_##i(const FwdArgs&, int, int, hipStream_t);
+DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8)
+#undef DECL
+static const FwdLauncher kFwdPagedLaunchers[kNumVariants] = {
+    fwd_paged_launch_0, fwd_paged_launch_1, fwd_paged_launch_2, fwd_paged_launch_3, fwd_paged_launch_4,
+    fwd_paged_launch_5, fwd_paged_launch_6, fwd_paged_launch_7, fwd_paged_launch_8};
 
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(int e) { g_last_hip_error = e; }
@@ -93,6 +99,48 @@ extern "C" int flexattn_forward(const flexattn_dims* dims, const flexattn_tensor
     a.scale = scale;
     if (params) a.p = *params;
     rc = kFwdLaunchers[vi](a, dims->D, bm->Bq, (hipStream_t)stream);
+    if (rc != FLEXATTN_OK) return rc;
+    FLEXATTN_HIP_TRY(hipGetLastError());
+    return FLEXATTN_OK;
+}
+
+extern "C" int flexattn_paged_forward(const flexattn_dims* dims, const flexattn_tensor* Q, const void* K_pool,
+                                      const void* V_pool, int32_t page_size, int32_t n_pool_pages, uint32_t score_id,
+                                      uint32_t mask_id, const flexattn_mod_params* params,
+                                      const flexattn_blockmask* bm, const int32_t* phys_kv_indices,
+                                      const int32_t* phys_full_kv_indices, float scale, const flexattn_tensor* O,
+                                      float* LSE, void* stream) {
+    int rc = check_problem(dims, bm);
+    if (rc != FLEXATTN_OK) return rc;
+    if ((rc = check_tensor(Q)) || (rc = check_tensor(O))) return rc;
+    if (!K_pool || !V_pool || ((uintptr_t)K_pool & 15) || ((uintptr_t)V_pool & 15)) return FLEXATTN_ERR_INVALID_ARG;
+    if (!phys_kv_indices || !phys_full_kv_indices || n_pool_pages <= 0) return FLEXATTN_ERR_INVALID_ARG;
+    if (!LSE || !(scale > 0.0f)) return FLEXATTN_ERR_INVALID_ARG;
+    if (page_size != bm->Bk) return FLEXATTN_ERR_UNSUPPORTED;     // a block of the BlockMask is a page
+    if (bm->Bm != dims->B) return FLEXATTN_ERR_INVALID_ARG;        // every sequence has its own pages
+    if ((rc = check_mod_params(mask_id, score_id, params)) != FLEXATTN_OK) return rc;
+    const int vi = find_variant(mask_id, score_id);
+    if (vi < 0) return FLEXATTN_ERR_UNSUPPORTED;
+
+    FwdArgs a = {};
+    a.Q = (const bf16*)Q->ptr; a.K = (const bf16*)K_pool; a.V = (const bf16*)V_pool;
+    a.O = (bf16*)O->ptr; a.LSE = LSE;
+    a.q_sb = Q->stride_b; a.q_sh = Q->stride_h; a.q_ss = Q->stride_s;
+    a.k_sb = 0; a.k_sh = (int64_t)page_size * dims->D; a.k_ss = dims->D;
+    a.v_sb = 0; a.v_sh = a.k_sh; a.v_ss = dims->D;
+    a.o_sb = O->stride_b; a.o_sh = O->stride_h; a.o_ss = O->stride_s;
+    a.B = dims->B; a.Hq = dims->Hq; a.Hkv = dims->Hkv; a.G = dims->Hq / dims->Hkv;
+    a.q_len = dims->q_len; a.kv_len = dims->kv_len;
+    a.NR = dims->q_len / bm->Bq; a.NC = dims->kv_len / bm->Bk; a.Bk = bm->Bk; a.sub = bm->Bk / kTileKV;
+    a.bm_Bm = bm->Bm; a.bm_Hm = bm->Hm;
+    a.kv_num = bm->kv_num_blocks; a.kv_idx = bm->kv_indices;
+    a.full_num = bm->full_kv_num_blocks; a.full_idx = bm->full_kv_indices;
+    a.phys_kv_idx = phys_kv_indices; a.phys_full_idx = phys_full_kv_indices;
+    a.page_stride = (int64_t)dims->Hkv * page_size * dims->D;
+    a.n_pool_pages = n_pool_pages;
+    a.scale = scale;
+    if (params) a.p = *params;
+    rc = kFwdPagedLaunchers[vi](a, dims->D, bm->Bq, (hipStream_t)stream);
     if (rc != FLEXATTN_OK) return rc;
     FLEXATTN_HIP_TRY(hipGetLastError());
     return FLEXATTN_OK;

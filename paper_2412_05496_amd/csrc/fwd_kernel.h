@@ -39,13 +39,22 @@ struct FwdArgs {
     const int32_t* full_idx;
     float scale;
     flexattn_mod_params p;
+    // paged K/V (section 5.1): K, V point at the pools, k_sb = v_sb = 0, k_sh = v_sh = page_size * D,
+    // k_ss = v_ss = D; page p starts page_stride elements after page p - 1; the physical block of
+    // every BlockMask entry stands at the same place in phys_kv_idx / phys_full_idx
+    const int32_t* phys_kv_idx;
+    const int32_t* phys_full_idx;
+    int64_t page_stride;
+    int n_pool_pages;
 };
 
 constexpr int kTileKV = 64;   // keys per kernel tile
 
 // BOUNDED: the score_mod ends in a soft-cap small enough that the cap itself serves as the fixed
 // softmax maximum (see ScoreMod::bounded); chosen by the host from the cap value.
-template <int D, int NW, uint32_t MASK, uint32_t SCORE, bool BOUNDED>
+// PAGED: the tiles of K and V are fetched from a paged pool through the converted block lists;
+// the mods keep seeing the logical key index.
+template <int D, int NW, uint32_t MASK, uint32_t SCORE, bool BOUNDED, bool PAGED = false>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     constexpr int Bq = NW * 32;
     constexpr int TILE = kTileKV * D;              // elements per LDS tile
@@ -89,23 +98,53 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *(const bf16x8*)(qp + ks * 16);
     }
-    const i32x4 k_rsrc = make_rsrc(a.K + b * a.k_sb + hkv * a.k_sh, (uint32_t)((a.kv_len - 1) * a.k_ss + D) * 2u);
-    const i32x4 v_rsrc = make_rsrc(a.V + b * a.v_sb + hkv * a.v_sh, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
+    const bf16* k_head = a.K + b * a.k_sb + hkv * a.k_sh;
+    const bf16* v_head = a.V + b * a.v_sb + hkv * a.v_sh;
+    const i32x4 k_rsrc = make_rsrc(k_head, (uint32_t)((a.kv_len - 1) * a.k_ss + D) * 2u);
+    const i32x4 v_rsrc = make_rsrc(v_head, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
     const int k_row_bytes = (int)a.k_ss * 2, v_row_bytes = (int)a.v_ss * 2;
+    // Where the 64 rows of a tile come from: a buffer descriptor and the byte offset of the first
+    // row in it.  Contiguous K/V: one descriptor per head, the tile chosen by the offset.  PAGED: a
+    // descriptor of exactly the tile, based at row `row` of pool page `page` (clamped to the pool,
+    // so that a wrong page table reads wrong rows and never faults).
+    auto tile_src = [&](const bf16* head, i32x4 whole, int row_bytes, int kv0, int page, int row, i32x4& rsrc,
+                        int& soff) __attribute__((always_inline)) {
+        if constexpr (PAGED) {
+            const int pg = min(max(page, 0), a.n_pool_pages - 1);
+            rsrc = make_rsrc(head + (int64_t)pg * a.page_stride + row * D, (uint32_t)(kTileKV * D * 2));
+            soff = 0;
+        } else {
+            rsrc = whole;
+            soff = kv0 * row_bytes;
+        }
+    };
 
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
-    const MaskRow<MASK> mrow(a.p, b, hq, q_row);
+    const int q_pos = q_row + q_offset_of(a.p, b);   // as the mods see it
+    const MaskRow<MASK> mrow(a.p, b, hq, q_pos);
     const float inv_neg2c = smod.capl2 > 0.0f ? -0.5f / smod.capl2 : 0.0f;   // 1 / (-2 cap log2 e)
 
     // first key and PARTIAL flag of tiles t, t+1, t+2 (the walk is always two tiles ahead)
-    TileWalk walk(a.full_idx + line * a.NC, a.kv_idx + line * a.NC, n_full, n_part, a.sub, a.Bk);
+    TileWalk<PAGED> walk(a.full_idx + line * a.NC, a.kv_idx + line * a.NC, n_full, n_part, a.sub, a.Bk,
+                         PAGED ? a.phys_full_idx + line * a.NC : nullptr, PAGED ? a.phys_kv_idx + line * a.NC : nullptr);
     int kv_t = 0, kv_t1 = 0, kv_t2 = 0;
     bool part_t = false, part_t1 = false, part_t2 = false;
+    int pg_t = 0, pg_t1 = 0, pg_t2 = 0, pr_t = 0, pr_t1 = 0, pr_t2 = 0;   // PAGED: page, row in page
     const uint32_t smem_bytes = lds_addr(smem);
     const WaveTileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
     // buf = tile index & 1
-    auto load_k = [&](int buf, int kv0) { k_loader.start(k_rsrc, smem_bytes + buf * (TILE * 2), kv0 * k_row_bytes); };
-    auto load_v = [&](int buf, int kv0) { v_loader.start(v_rsrc, smem_bytes + (2 + buf) * (TILE * 2), kv0 * v_row_bytes); };
+    auto load_k = [&](int buf, int kv0, int page, int row) {
+        i32x4 rsrc;
+        int soff;
+        tile_src(k_head, k_rsrc, k_row_bytes, kv0, page, row, rsrc, soff);
+        k_loader.start(rsrc, smem_bytes + buf * (TILE * 2), soff);
+    };
+    auto load_v = [&](int buf, int kv0, int page, int row) {
+        i32x4 rsrc;
+        int soff;
+        tile_src(v_head, v_rsrc, v_row_bytes, kv0, page, row, rsrc, soff);
+        v_loader.start(rsrc, smem_bytes + (2 + buf) * (TILE * 2), soff);
+    };
     const RowReader<D> k_reader(l32, half);
     const TrReader<D> v_reader(lane);
 
@@ -138,7 +177,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     // kvs: s -> P^T as two bf16 fragments.  The mask is a separate, rarely taken pass (kept a real
     // branch) so that the common path is one straight run of VALU work next to the MFMAs around it.
     auto softmax = [&](f32x16& s, int kvs, bool partial, bf16x8 (&pf)[2]) {
-        const int dq_base = q_row - kvs;
+        const int dq_base = q_pos - kvs;
         if constexpr (BOUNDED) {
             // p = 2^(x - cap log2 e) = 2^(-2 cap log2 e * r), r = 1 / (1 + e): no maximum to track
 #pragma unroll
@@ -205,12 +244,12 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     };
 
     // ---- prologue: K(0), V(0), K(1) in flight; S^T(0)
-    kv_t = walk.next(part_t);
-    load_k(0, kv_t);
-    load_v(0, kv_t);
+    kv_t = walk.next(part_t, pg_t, pr_t);
+    load_k(0, kv_t, pg_t, pr_t);
+    load_v(0, kv_t, pg_t, pr_t);
     if (T > 1) {
-        kv_t1 = walk.next(part_t1);
-        load_k(1, kv_t1);
+        kv_t1 = walk.next(part_t1, pg_t1, pr_t1);
+        load_k(1, kv_t1, pg_t1, pr_t1);
     }
     wait_vmem();
     __syncthreads();
@@ -230,7 +269,11 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
         // every load instruction until the memory pipe has taken it, and a burst of them from all
         // waves at once keeps everybody waiting
         const bool ld_k = t + 2 < T;
-        if (ld_k) kv_t2 = walk.next(part_t2);
+        if (ld_k) kv_t2 = walk.next(part_t2, pg_t2, pr_t2);
+        i32x4 k_src, v_src;
+        int k_soff, v_soff;
+        tile_src(k_head, k_rsrc, k_row_bytes, kv_t2, pg_t2, pr_t2, k_src, k_soff);
+        tile_src(v_head, v_rsrc, v_row_bytes, kv_t1, pg_t1, pr_t1, v_src, v_soff);
         const int kv0 = kv_t;
         const bool partial = part_t;
         bf16x8 pf[2];
@@ -242,10 +285,9 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
                     constexpr int p = decltype(p_tag)::value;
                     if constexpr (p * NMQ / NP == decltype(m_tag)::value) {
                         if constexpr (p < L::NI) {
-                            if (ld_k) k_loader.template start_one<p>(k_rsrc, smem_bytes + BUF * (TILE * 2), kv_t2 * k_row_bytes);
+                            if (ld_k) k_loader.template start_one<p>(k_src, smem_bytes + BUF * (TILE * 2), k_soff);
                         } else {
-                            v_loader.template start_one<p - L::NI>(v_rsrc, smem_bytes + (2 + (BUF ^ 1)) * (TILE * 2),
-                                                                   kv_t1 * v_row_bytes);
+                            v_loader.template start_one<p - L::NI>(v_src, smem_bytes + (2 + (BUF ^ 1)) * (TILE * 2), v_soff);
                         }
                     }
                 });
@@ -261,6 +303,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
         }
         kv_t = kv_t1, part_t = part_t1;
         kv_t1 = kv_t2, part_t1 = part_t2;
+        if constexpr (PAGED) pg_t1 = pg_t2, pr_t1 = pr_t2;
     };
     {
         const std::integral_constant<int, 0> b0;
@@ -293,12 +336,12 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     if (half == 0) *lse_ptr = l_tot > 0.0f ? (m_run + fast_log2(l_tot)) * kLn2 : -INFINITY;
 }
 
-template <uint32_t MASK, uint32_t SCORE, bool BOUNDED>
+template <uint32_t MASK, uint32_t SCORE, bool BOUNDED, bool PAGED>
 int launch_fwd_shape(const FwdArgs& a, int D, int Bq, hipStream_t st) {
     const int units = a.B * a.Hkv;
     const unsigned grid = (unsigned)(((units + 7) / 8) * 8 * a.G * a.NR);
 #define FLEXATTN_LAUNCH(DD, NW)                                                                            \
-    hipLaunchKernelGGL((fwd_kernel<DD, NW, MASK, SCORE, BOUNDED>), dim3(grid), dim3(NW * 64), 0, st, a);   \
+    hipLaunchKernelGGL((fwd_kernel<DD, NW, MASK, SCORE, BOUNDED, PAGED>), dim3(grid), dim3(NW * 64), 0, st, a); \
     return FLEXATTN_OK;
     if (D == 128 && Bq == 128) { FLEXATTN_LAUNCH(128, 4) }
     if (D == 128 && Bq == 64) { FLEXATTN_LAUNCH(128, 2) }
@@ -308,12 +351,12 @@ int launch_fwd_shape(const FwdArgs& a, int D, int Bq, hipStream_t st) {
     return FLEXATTN_ERR_UNSUPPORTED;
 }
 
-template <uint32_t MASK, uint32_t SCORE>
+template <uint32_t MASK, uint32_t SCORE, bool PAGED = false>
 int launch_fwd_variant(const FwdArgs& a, int D, int Bq, hipStream_t st) {
     if constexpr (SCORE & FLEXATTN_SCORE_SOFTCAP) {
-        if (2.0f * a.p.softcap * kLog2e <= 100.0f) return launch_fwd_shape<MASK, SCORE, true>(a, D, Bq, st);
+        if (2.0f * a.p.softcap * kLog2e <= 100.0f) return launch_fwd_shape<MASK, SCORE, true, PAGED>(a, D, Bq, st);
     }
-    return launch_fwd_shape<MASK, SCORE, false>(a, D, Bq, st);
+    return launch_fwd_shape<MASK, SCORE, false, PAGED>(a, D, Bq, st);
 }
 
 }  // namespace flexattn

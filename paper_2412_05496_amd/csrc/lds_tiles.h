@@ -186,32 +186,53 @@ struct TrReader {
 // FULL blocks first, then PARTIAL ones, each block cut into `sub` tiles.  Written without
 // branches, and the index of the following block is fetched (scalar cache) on every call and only
 // consumed by the call after it, so that the fetch has a tile's worth of work to hide behind.
+template <bool PAGED = false>
 struct TileWalk {
     const int32_t* full_idx;
     const int32_t* part_idx;
+    const int32_t* full_phys;                   // PAGED: the converted lists (section 5.1), read entry
+    const int32_t* part_phys;                   // by entry beside the logical ones
     int n_full, n_blocks, sub, block_len;
-    int pos, s, blk, fetched;
+    int pos, s, blk, fetched, pblk, pfetched;
     bool entered;                               // the previous call moved on to the next block
     __device__ __forceinline__ int block_at(int p) const {
         return ldc(p < n_full ? full_idx + p : part_idx + (p - n_full));
     }
+    __device__ __forceinline__ int phys_at(int p) const {
+        return ldc(p < n_full ? full_phys + p : part_phys + (p - n_full));
+    }
     __device__ __forceinline__ TileWalk(const int32_t* full_idx_, const int32_t* part_idx_, int n_full_, int n_part,
-                                        int sub_, int block_len_)
-        : full_idx(full_idx_), part_idx(part_idx_), n_full(n_full_), n_blocks(n_full_ + n_part), sub(sub_),
-          block_len(block_len_), pos(0), s(0), fetched(0), entered(false) {
+                                        int sub_, int block_len_, const int32_t* full_phys_ = nullptr,
+                                        const int32_t* part_phys_ = nullptr)
+        : full_idx(full_idx_), part_idx(part_idx_), full_phys(full_phys_), part_phys(part_phys_), n_full(n_full_),
+          n_blocks(n_full_ + n_part), sub(sub_), block_len(block_len_), pos(0), s(0), fetched(0), pblk(0),
+          pfetched(0), entered(false) {
         blk = n_blocks > 0 ? block_at(0) : 0;
+        if constexpr (PAGED) pblk = n_blocks > 0 ? phys_at(0) : 0;
     }
     // first row (column) of the next tile, and whether its block is PARTIAL; must not be called
-    // more than n_blocks * sub times
-    __device__ __forceinline__ int next(bool& partial) {
+    // more than n_blocks * sub times.  PAGED: `page` and `row_in_page` receive where the tile starts
+    // in the pool (the page is the physical block); otherwise they are not touched.
+    __device__ __forceinline__ int next(bool& partial, int& page, int& row_in_page) {
         blk = entered ? fetched : blk;
         const int x0 = blk * block_len + s * 64;
+        if constexpr (PAGED) {
+            pblk = entered ? pfetched : pblk;
+            page = pblk;
+            row_in_page = s * 64;
+            pfetched = phys_at(min(pos + 1, n_blocks - 1));
+        }
         partial = pos >= n_full;
         fetched = block_at(min(pos + 1, n_blocks - 1));
         entered = s + 1 == sub;
         s = entered ? 0 : s + 1;
         pos += entered ? 1 : 0;
         return x0;
+    }
+    __device__ __forceinline__ int next(bool& partial) {
+        static_assert(!PAGED, "the paged walk also yields the physical position");
+        int page, row;
+        return next(partial, page, row);
     }
 };
 

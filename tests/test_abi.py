@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     lib = binding._lib()
     names = declared_symbols()
     assert {"flexattn_blockmask_build", "flexattn_forward", "flexattn_backward", "flexattn_paged_decode",
-            "flexattn_paged_convert_blockmask"} <= set(names)
+            "flexattn_paged_convert_blockmask", "flexattn_paged_forward"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -60,6 +60,17 @@ def test_null_and_bad_arguments_are_rejected_on_the_host():
     bm = binding._BlockMask(1, 1, 128, 128, 32, 64, 1, 1, 1, 1, 1, 1, 1, 1)   # Bq = 32 unsupported
     assert lib.flexattn_forward(C.byref(d), None, None, None, 0, 0, None, C.byref(bm), 1.0, None, None,
                                 None) == fa.ERR_UNSUPPORTED
+    # paged forward: a page must be a BlockMask block, and every sequence needs its own lists
+    t = binding._Tensor(16, 0, 0, 128)
+    bm = binding._BlockMask(2, 1, 128, 256, 128, 64, 1, 1, 1, 1, 1, 1, 1, 1)
+    d = binding._Dims(2, 2, 2, 128, 256, 128)
+    args = (0, 0, None, C.byref(bm), 16, 16, 1.0, C.byref(t), 16, None)
+    assert lib.flexattn_paged_forward(C.byref(d), C.byref(t), 16, 16, 128, 8, *args) == fa.ERR_UNSUPPORTED
+    assert lib.flexattn_paged_forward(C.byref(d), C.byref(t), 16, 16, 64, 0, *args) == fa.ERR_INVALID_ARG
+    assert lib.flexattn_paged_forward(C.byref(d), C.byref(t), 16, 24, 64, 8, *args) == fa.ERR_INVALID_ARG
+    bm1 = binding._BlockMask(1, 1, 128, 256, 128, 64, 1, 1, 1, 1, 1, 1, 1, 1)
+    args1 = (0, 0, None, C.byref(bm1), 16, 16, 1.0, C.byref(t), 16, None)
+    assert lib.flexattn_paged_forward(C.byref(d), C.byref(t), 16, 16, 64, 8, *args1) == fa.ERR_INVALID_ARG
     # ragged sequence (q_len % Bq != 0) is refused by the builder
     bm = binding._BlockMask(1, 1, 100, 128, 64, 64, 1, 1, 1, 1, 1, 1, 1, 1)
     assert lib.flexattn_blockmask_build(fa.MASK_CAUSAL, None, C.byref(bm), None, 1, 1 << 20, None) == fa.ERR_INVALID_ARG
