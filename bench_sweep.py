@@ -1,8 +1,9 @@
 """Sweep over the shapes of the paper's kernel benchmarks (section 6.2: head dimension 64, KV size fixed
 at 256 MiB, causal attention from 1k to 64k tokens; seven variants at 16k tokens with and without GQA;
-section 4.2: the full / partial split; section 6.2 / 6.4: decode from 1k to 132k tokens and page sizes).
+section 4.2: the full / partial split; section 6.2 / 6.4: decode from 1k to 132k tokens and page sizes;
+sections 5.1 + 5.2: a chunk of query tokens against a paged cache, beside the same chunk on a contiguous cache).
 
-    python bench_sweep.py [--part train|variants|split|decode|pages|all] [--iters N]
+    python bench_sweep.py [--part train|variants|split|decode|pages|prefill|all] [--iters N]
 
 One JSON line per measured point (synthetic seeded inputs, bf16, one MI355X).  TFLOP/s count UNMASKED
 FLOPs only (4 D per pair forward, 10 D backward); decode is HBM GB/s of the K/V bytes of the tokens read.
@@ -126,9 +127,44 @@ def decode_point(fa, wlm, wl, iters, tag, dev, identity_table=False):
                       "kv_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}), flush=True)
 
 
+def prefill_point(fa, wlm, wl, kv_len, q_len, iters, dev):
+    """Causal chunk of q_len tokens at the end of kv_len-token sequences: paged pool, then the same
+    keys gathered into a contiguous [B, Hkv, kv_len, D] cache (same BlockMask, same offsets)."""
+    import torch
+    inp = wlm.make_prefill_inputs(wl, [kv_len] * wl.B, q_len)
+    page, n_pool = wl.page_size, inp.K_pool.shape[0]
+    params = fa.ModParams(q_offsets=inp.q_offsets.to(dev))
+    bm = fa.alloc_blockmask(wl.B, 1, q_len, kv_len, wl.Bq, page, device=dev)
+    fa.flexattn_blockmask_build(fa.MASK_CAUSAL, params, bm)
+    pt = inp.page_table.to(dev)
+    phys_kv, phys_full = torch.zeros_like(bm.kv_indices), torch.zeros_like(bm.full_kv_indices)
+    fa.flexattn_paged_convert_blockmask(bm.kv_num_blocks, bm.kv_indices, pt, phys_kv)
+    fa.flexattn_paged_convert_blockmask(bm.full_kv_num_blocks, bm.full_kv_indices, pt, phys_full)
+    torch.cuda.synchronize()
+    pairs = bm.stats.cpu().tolist()[3] * wl.Hq
+    Q, Kp, Vp = inp.Q.to(dev), inp.K_pool.to(dev), inp.V_pool.to(dev)
+    O = torch.empty_like(Q)
+    LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=dev)
+    t_paged = event_ms(lambda: fa.flexattn_paged_forward(Q, Kp, Vp, fa.SCORE_IDENTITY, fa.MASK_CAUSAL, params, bm, phys_kv,
+                                                         phys_full, inp.scale, O, LSE), iters)
+    O_paged = O.clone()
+    pages = kv_len // page
+    gather = lambda pool: (pool[pt[:, :pages].long()]                      # [B, pages, Hkv, page, D]
+                           .permute(0, 2, 1, 3, 4).reshape(wl.B, wl.Hkv, kv_len, wl.D).contiguous())
+    Kc, Vc = gather(Kp), gather(Vp)
+    t_contig = event_ms(lambda: fa.flexattn_forward(Q, Kc, Vc, fa.SCORE_IDENTITY, fa.MASK_CAUSAL, params, bm, inp.scale,
+                                                    O, LSE), iters)
+    print(json.dumps({"part": "prefill", "nseq": wl.B, "kv_len": kv_len, "q_len": q_len, "Hq": wl.Hq, "Hkv": wl.Hkv,
+                      "D": wl.D, "page_size": page, "pairs": pairs, "paged_ms": round(t_paged, 4),
+                      "contiguous_ms": round(t_contig, 4),
+                      "paged_tflops": round(4 * wl.D * pairs / (t_paged * 1e-3) / 1e12, 1),
+                      "contiguous_tflops": round(4 * wl.D * pairs / (t_contig * 1e-3) / 1e12, 1),
+                      "same_output": bool(torch.equal(O_paged, O))}), flush=True)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--part", default="all", choices=["train", "variants", "split", "decode", "pages", "all"])
+    ap.add_argument("--part", default="all", choices=["train", "variants", "split", "decode", "pages", "prefill", "all"])
     ap.add_argument("--iters", type=int, default=10)
     args = ap.parse_args()
 
@@ -139,7 +175,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     W = wlm.Workload
-    parts = [args.part] if args.part != "all" else ["train", "variants", "split", "decode", "pages"]
+    parts = [args.part] if args.part != "all" else ["train", "variants", "split", "decode", "pages", "prefill"]
 
     if "train" in parts:        # causal, D = 64, H = 16, B * S = 65536 (K + V = 256 MiB)
         for S in (1024, 2048, 4096, 8192, 16384, 32768, 65536):
@@ -175,6 +211,13 @@ def main() -> int:
                        score="identity", seed=2400 + page, backward=False, page_size=page, ctx_min=16384,
                        ctx_max=16384, max_pages=16384 // page)
                 decode_point(fa, wlm, wl, args.iters, "pages", dev, identity_table=ident)
+    if "prefill" in parts:     # chunked prefill: 2048 new tokens on top of 16k / 64k cached, pages of 64 / 128
+        for page in (64, 128):
+            for nseq, kv_len in ((16, 16384), (4, 65536)):
+                wl = W(f"sweep_prefill_{page}_{kv_len}", B=nseq, Hq=32, Hkv=8, S=2048, D=128, Bq=128, Bk=page,
+                       mask="causal", score="identity", seed=2500 + page + kv_len // 1024, backward=False,
+                       page_size=page, ctx_min=kv_len, ctx_max=kv_len, max_pages=kv_len // page)
+                prefill_point(fa, wlm, wl, kv_len, 2048, args.iters, dev)
     return 0
 
 
