@@ -28,6 +28,9 @@ What follows what (paper = arXiv 2412.05496):
 * ``paged_attention``           sections 5.1 + 5.2 for a chunk of several query tokens per sequence
                                 (chunked prefill): un-page, then Eq. 1 with the mods shifted
                                 by each sequence's offset.
+* ``neighborhood_mask``         appendix (Neighborhood Attention): every pixel of a 2-D canvas attends
+                                to its K x K nearest pixels; the tokens are laid out row by row,
+                                in 2-D tiles, or along the Morton curve.
 * ``flex_attention_backward``   the paper only states that a backward template
                                 exists (section 4.1); this is ordinary calculus on
                                 Eq. 1, pinned by finite differences in the tests.
@@ -472,3 +475,55 @@ def paged_attention(Q, K_pool, V_pool, page_table, kv_lens, q_offsets, score_mod
         for h in range(Hq):
             O[b, h], LSE[b, h] = attention_head(Q[b, h], Kl[h // G], Vl[h // G], score_inf, mask_inf, scale, b, h)
     return O, LSE
+
+
+# --------------------------------------------------------------------------
+# Neighborhood attention on a 2-D canvas (appendix, "Neighborhood Attention (NA)")
+# --------------------------------------------------------------------------
+def _spread_bits(v: int) -> int:
+    """Bit i of v moves to bit 2 i."""
+    out, i = 0, 0
+    while v >> i:
+        out |= ((v >> i) & 1) << (2 * i)
+        i += 1
+    return out
+
+
+def na_token_index(x: int, y: int, width: int, height: int, layout: str, tile: int = 0) -> int:
+    """Where pixel (x, y) of a width x height canvas sits in the token sequence.
+    row_major: row after row.  tiled: tile x tile squares, the squares row after row, the pixels of
+    a square row after row.  morton: bits of x and y interleaved, x in the even positions."""
+    if layout == "row_major":
+        return y * width + x
+    if layout == "tiled":
+        assert width % tile == 0 and height % tile == 0
+        return ((y // tile) * (width // tile) + x // tile) * tile * tile + (y % tile) * tile + x % tile
+    if layout == "morton":
+        assert width == height and width & (width - 1) == 0
+        return _spread_bits(x) | (_spread_bits(y) << 1)
+    raise ValueError(layout)
+
+
+def na_token_xy(width: int, height: int, layout: str, tile: int = 0):
+    """(xs, ys): pixel of every token, by enumerating the canvas through na_token_index."""
+    xs = torch.empty(width * height, dtype=torch.int64)
+    ys = torch.empty(width * height, dtype=torch.int64)
+    for y in range(height):
+        for x in range(width):
+            i = na_token_index(x, y, width, height, layout, tile)
+            xs[i], ys[i] = x, y
+    return xs, ys
+
+
+def neighborhood_mask(width: int, height: int, kernel: int, layout: str = "row_major", tile: int = 0) -> MaskMod:
+    """A query pixel attends to the kernel x kernel pixels nearest to it: the window centred on the
+    pixel, moved inside the canvas where it would stick out (every query sees exactly kernel^2 keys)."""
+    assert kernel % 2 == 1 and kernel <= width and kernel <= height
+    xs, ys = na_token_xy(width, height, layout, tile)
+    r = kernel // 2
+
+    def mod(b, h, q_idx, kv_idx):
+        cx = xs[q_idx].clamp(r, width - 1 - r)
+        cy = ys[q_idx].clamp(r, height - 1 - r)
+        return ((cx - xs[kv_idx]).abs() <= r) & ((cy - ys[kv_idx]).abs() <= r)
+    return mod
