@@ -1,9 +1,10 @@
 """Sweep over the shapes of the paper's kernel benchmarks (section 6.2: head dimension 64, KV size fixed
 at 256 MiB, causal attention from 1k to 64k tokens; seven variants at 16k tokens with and without GQA;
 section 4.2: the full / partial split; section 6.2 / 6.4: decode from 1k to 132k tokens and page sizes;
-sections 5.1 + 5.2: a chunk of query tokens against a paged cache, beside the same chunk on a contiguous cache).
+sections 5.1 + 5.2: a chunk of query tokens against a paged cache, beside the same chunk on a contiguous cache;
+appendix: neighborhood attention in row-major, tiled and Morton token order over canvas and kernel sizes).
 
-    python bench_sweep.py [--part train|variants|split|decode|pages|prefill|all] [--iters N]
+    python bench_sweep.py [--part train|variants|split|decode|pages|prefill|na|all] [--iters N]
 
 One JSON line per measured point (synthetic seeded inputs, bf16, one MI355X).  TFLOP/s count UNMASKED
 FLOPs only (4 D per pair forward, 10 D backward); decode is HBM GB/s of the K/V bytes of the tokens read.
@@ -162,9 +163,42 @@ def prefill_point(fa, wlm, wl, kv_len, q_len, iters, dev):
                       "same_output": bool(torch.equal(O_paged, O))}), flush=True)
 
 
+def na_point(fa, wlm, canvas, kernel, layout, tile, iters, dev):
+    """Neighborhood attention on a canvas x canvas image, 4 x 16 heads of 64: block density, forward, backward."""
+    import torch
+    S = canvas * canvas
+    wl = wlm.Workload(f"sweep_na_{canvas}_{kernel}_{layout}", B=4, Hq=16, Hkv=16, S=S, D=64, Bq=128, Bk=64, mask="none",
+                      score="identity", seed=2600 + canvas + kernel)
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    params = fa.ModParams(na_width=canvas, na_height=canvas, na_kernel=kernel,
+                          na_layout={"row_major": fa.NA_ROW_MAJOR, "tiled": fa.NA_TILED, "morton": fa.NA_MORTON}[layout],
+                          na_tile=tile)
+    bm = fa.alloc_blockmask(1, 1, S, S, wl.Bq, wl.Bk, device=dev)
+    fa.flexattn_blockmask_build(fa.MASK_NEIGHBORHOOD, params, bm)
+    torch.cuda.synchronize()
+    stats = bm.stats.cpu().tolist()
+    pairs = stats[3] * wl.B * wl.Hq
+    Q, K, V, dO = (t.to(dev) for t in (inp.Q, inp.K, inp.V, inp.dO))
+    O = torch.empty_like(Q)
+    LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=dev)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    ws = torch.empty(fa.flexattn_backward_workspace_bytes(Q, K), dtype=torch.uint8, device=dev)
+    fwd = lambda: fa.flexattn_forward(Q, K, V, fa.SCORE_IDENTITY, fa.MASK_NEIGHBORHOOD, params, bm, inp.scale, O, LSE)
+    bwd = lambda: fa.flexattn_backward_stages(Q, K, V, O, dO, LSE, fa.SCORE_IDENTITY, fa.MASK_NEIGHBORHOOD, params, bm,
+                                              inp.scale, dQ, dK, dV, ws, fa.BWD_ALL)
+    t_f, t_b = event_ms(fwd, iters), event_ms(bwd, iters)
+    print(json.dumps({
+        "part": "na", "canvas": canvas, "kernel": kernel, "layout": layout, "tile": tile, "tokens": S,
+        "mask_density": round(stats[3] / (S * S), 5),
+        "block_density": round((stats[0] + stats[1]) / stats[2], 5),
+        "blocks_partial_full_total": stats[:3], "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4),
+        "fwd_tflops": round(4 * wl.D * pairs / (t_f * 1e-3) / 1e12, 1),
+        "bwd_tflops": round(10 * wl.D * pairs / (t_b * 1e-3) / 1e12, 1)}), flush=True)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--part", default="all", choices=["train", "variants", "split", "decode", "pages", "prefill", "all"])
+    ap.add_argument("--part", default="all", choices=["train", "variants", "split", "decode", "pages", "prefill", "na", "all"])
     ap.add_argument("--iters", type=int, default=10)
     args = ap.parse_args()
 
@@ -175,7 +209,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     W = wlm.Workload
-    parts = [args.part] if args.part != "all" else ["train", "variants", "split", "decode", "pages", "prefill"]
+    parts = [args.part] if args.part != "all" else ["train", "variants", "split", "decode", "pages", "prefill", "na"]
 
     if "train" in parts:        # causal, D = 64, H = 16, B * S = 65536 (K + V = 256 MiB)
         for S in (1024, 2048, 4096, 8192, 16384, 32768, 65536):
@@ -218,6 +252,11 @@ def main() -> int:
                        mask="causal", score="identity", seed=2500 + page + kv_len // 1024, backward=False,
                        page_size=page, ctx_min=kv_len, ctx_max=kv_len, max_pages=kv_len // page)
                 prefill_point(fa, wlm, wl, kv_len, 2048, args.iters, dev)
+    if "na" in parts:          # canvas 64 / 128, kernels 7 / 13 / 27, three token orders (8 x 8 tiles)
+        for canvas in (64, 128):
+            for kernel in (7, 13, 27):
+                for layout, tile in (("row_major", 0), ("tiled", 8), ("morton", 0)):
+                    na_point(fa, wlm, canvas, kernel, layout, tile, args.iters, dev)
     return 0
 
 

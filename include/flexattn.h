@@ -56,6 +56,11 @@ extern "C" {
 #define FLEXATTN_M_DOCUMENT        4u   /* doc_ids[b, q_idx] == doc_ids[b, kv_idx]                */
 #define FLEXATTN_M_PREFIX          8u   /* kv_idx < prefix_len                                    */
 #define FLEXATTN_M_CTX_LEN        16u   /* kv_idx < ctx_lens[b]                                   */
+#define FLEXATTN_M_NEIGHBORHOOD   32u   /* neighborhood attention on a 2-D canvas (appendix "NA"):
+                                           the tokens are the pixels of an na_width x na_height
+                                           canvas; a query pixel sees the na_kernel x na_kernel
+                                           pixels nearest to it (the window centred on it, moved
+                                           inside the canvas where it would stick out)           */
 #define FLEXATTN_MASK_OR(term0, term1) ((uint32_t)(term0) | ((uint32_t)(term1) << 8))
 
 #define FLEXATTN_MASK_NONE                  0u
@@ -68,6 +73,16 @@ extern "C" {
 #define FLEXATTN_MASK_SWA_CAUSAL_OR_PREFIX  FLEXATTN_MASK_OR(FLEXATTN_MASK_SWA_CAUSAL, FLEXATTN_M_PREFIX)
 #define FLEXATTN_MASK_CTX_LEN               FLEXATTN_M_CTX_LEN
 #define FLEXATTN_MASK_CTX_LEN_WINDOW        (FLEXATTN_M_CTX_LEN | FLEXATTN_M_SLIDING_WINDOW)
+#define FLEXATTN_MASK_NEIGHBORHOOD          FLEXATTN_M_NEIGHBORHOOD
+
+/* Token order of the canvas for NEIGHBORHOOD (pixel (x, y) -> token index):
+ *   ROW_MAJOR  y * W + x
+ *   TILED      T x T squares, the squares row after row, the pixels of a square row after row:
+ *              ((y / T) * (W / T) + x / T) * T * T + (y % T) * T + x % T
+ *   MORTON     the bits of x and y interleaved, x in the even positions (Z-order curve) */
+#define FLEXATTN_NA_ROW_MAJOR 0
+#define FLEXATTN_NA_TILED     1
+#define FLEXATTN_NA_MORTON    2
 
 /* ---- score_mod (section 3.1; nested score_mods, section 1.1) -------------------------
  * A bit set; the selected modifications are applied to the scaled score in this order:
@@ -95,6 +110,12 @@ typedef struct flexattn_mod_params {
                                      offset conversion for inference of section 5.2 (number of
                                      tokens of sequence b processed before this call's first
                                      query); BlockMask build, forward and backward honour it    */
+    int32_t        na_width;      /* NEIGHBORHOOD: canvas W x H; q_len == kv_len == W * H <= 2^20 */
+    int32_t        na_height;
+    int32_t        na_kernel;     /*   odd K, 1 <= K <= min(W, H): K x K keys per query          */
+    int32_t        na_layout;     /*   FLEXATTN_NA_*                                              */
+    int32_t        na_tile;       /*   TILED: T, a power of two that divides W and H;
+                                       MORTON needs W == H == a power of two                     */
 } flexattn_mod_params;
 
 /* A 4-D tensor [batch, head, seq, D] with unit stride in D.  ptr is 16-byte aligned, the

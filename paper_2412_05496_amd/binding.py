@@ -16,7 +16,7 @@ import torch
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libflexattn.so")
 
 # ---- ids (mirrors of the #defines in flexattn.h) -----------------------------------------
-M_CAUSAL, M_SLIDING_WINDOW, M_DOCUMENT, M_PREFIX, M_CTX_LEN = 1, 2, 4, 8, 16
+M_CAUSAL, M_SLIDING_WINDOW, M_DOCUMENT, M_PREFIX, M_CTX_LEN, M_NEIGHBORHOOD = 1, 2, 4, 8, 16, 32
 
 
 def mask_or(term0: int, term1: int) -> int:
@@ -33,6 +33,8 @@ MASK_PREFIX_LM = mask_or(M_CAUSAL, M_PREFIX)
 MASK_SWA_CAUSAL_OR_PREFIX = mask_or(MASK_SWA_CAUSAL, M_PREFIX)
 MASK_CTX_LEN = M_CTX_LEN
 MASK_CTX_LEN_WINDOW = M_CTX_LEN | M_SLIDING_WINDOW
+MASK_NEIGHBORHOOD = M_NEIGHBORHOOD
+NA_ROW_MAJOR, NA_TILED, NA_MORTON = 0, 1, 2
 
 SCORE_IDENTITY, SCORE_ALIBI, SCORE_REL_BIAS, SCORE_SOFTCAP = 0, 1, 2, 4
 
@@ -51,7 +53,9 @@ class FlexAttnError(RuntimeError):
 class _ModParams(C.Structure):
     _fields_ = [("window", C.c_int32), ("prefix_len", C.c_int32), ("softcap", C.c_float), ("rel_len", C.c_int32),
                 ("doc_ids", C.c_void_p), ("doc_stride_b", C.c_int64), ("alibi_bias", C.c_void_p),
-                ("rel_bias", C.c_void_p), ("ctx_lens", C.c_void_p), ("q_offsets", C.c_void_p)]
+                ("rel_bias", C.c_void_p), ("ctx_lens", C.c_void_p), ("q_offsets", C.c_void_p),
+                ("na_width", C.c_int32), ("na_height", C.c_int32), ("na_kernel", C.c_int32),
+                ("na_layout", C.c_int32), ("na_tile", C.c_int32)]
 
 
 class _Tensor(C.Structure):
@@ -159,10 +163,17 @@ class ModParams:
     rel_bias: Optional[torch.Tensor] = None      # fp32 [Hq, rel_len]
     ctx_lens: Optional[torch.Tensor] = None      # int32 [B]
     q_offsets: Optional[torch.Tensor] = None     # int32 [B]: the mods see q_idx + q_offsets[b]
+    na_width: int = 0                            # neighborhood attention: canvas, kernel, token order
+    na_height: int = 0
+    na_kernel: int = 0
+    na_layout: int = 0
+    na_tile: int = 0
 
     def _c(self) -> _ModParams:
         p = _ModParams()
         p.window, p.prefix_len, p.softcap = int(self.window), int(self.prefix_len), float(self.softcap)
+        p.na_width, p.na_height, p.na_kernel = int(self.na_width), int(self.na_height), int(self.na_kernel)
+        p.na_layout, p.na_tile = int(self.na_layout), int(self.na_tile)
         if self.doc_ids is not None:
             assert self.doc_ids.dtype == torch.int32 and self.doc_ids.is_cuda and self.doc_ids.stride(-1) == 1
             p.doc_ids = self.doc_ids.data_ptr()

@@ -140,6 +140,7 @@ extern "C" int flexattn_blockmask_build(uint32_t mask_id, const flexattn_mod_par
         return FLEXATTN_ERR_INVALID_ARG;
     int rc = check_mod_params(mask_id, 0, params);
     if (rc != FLEXATTN_OK) return rc;
+    if ((rc = check_canvas(mask_id, params, bm->q_len, bm->kv_len)) != FLEXATTN_OK) return rc;
     if (bm->q_len % bm->Bq != 0 || bm->kv_len % bm->Bk != 0) return FLEXATTN_ERR_UNSUPPORTED;
     const int NR = bm->q_len / bm->Bq, NC = bm->kv_len / bm->Bk;
     const long long nblocks = (long long)bm->Bm * bm->Hm * NR * NC;
@@ -166,6 +167,7 @@ extern "C" int flexattn_blockmask_build(uint32_t mask_id, const flexattn_mod_par
         CASE(FLEXATTN_MASK_PREFIX_LM)
         CASE(FLEXATTN_MASK_SWA_CAUSAL_OR_PREFIX)
         CASE(FLEXATTN_MASK_CTX_LEN)
+        CASE(FLEXATTN_MASK_NEIGHBORHOOD)
         CASE((FLEXATTN_M_CTX_LEN | FLEXATTN_M_CAUSAL))
         CASE((FLEXATTN_MASK_SWA_CAUSAL | FLEXATTN_M_DOCUMENT))
 #undef CASE

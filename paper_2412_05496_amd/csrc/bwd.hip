@@ -5,12 +5,13 @@
 namespace flexattn {
 
 #define DECL(i) int bwd_launch_##i(const BwdArgs&, int, uint32_t, hipStream_t);
-DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8)
+DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8) DECL(9)
 #undef DECL
 typedef int (*BwdLauncher)(const BwdArgs&, int, uint32_t, hipStream_t);
 static const BwdLauncher kBwdLaunchers[kNumVariants] = {bwd_launch_0, bwd_launch_1, bwd_launch_2,
                                                         bwd_launch_3, bwd_launch_4, bwd_launch_5,
-                                                        bwd_launch_6, bwd_launch_7, bwd_launch_8};
+                                                        bwd_launch_6, bwd_launch_7, bwd_launch_8,
+                                                        bwd_launch_9};
 int check_tensor(const flexattn_tensor* t);
 int check_extent(const flexattn_tensor* t, int len, int D);
 int check_problem(const flexattn_dims* d, const flexattn_blockmask* bm);
@@ -51,6 +52,7 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
     if (!bm->q_num_blocks || !bm->q_indices || !bm->full_q_num_blocks || !bm->full_q_indices)
         return FLEXATTN_ERR_INVALID_ARG;
     if ((rc = check_mod_params(mask_id, score_id, params)) != FLEXATTN_OK) return rc;
+    if ((rc = check_canvas(mask_id, params, dims->q_len, dims->kv_len)) != FLEXATTN_OK) return rc;
     const int vi = find_variant(mask_id, score_id);
     if (vi < 0) return FLEXATTN_ERR_UNSUPPORTED;
     if (ws_bytes < flexattn_backward_workspace_bytes(dims)) return FLEXATTN_ERR_WORKSPACE;

@@ -75,17 +75,80 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // mask_mod: OR of up to two AND-terms over the primitive predicates.
 // A MaskRow caches what depends only on (b, h, q_idx); operator() takes kv_idx.
 // ---------------------------------------------------------------------------------------
+// Token index -> pixel of the canvas, for the neighborhood mask (appendix, Neighborhood Attention).
+struct CanvasOrder {
+    int width, layout, tile_log2, tiles_x;
+    float inv_width, inv_tiles_x;
+    __device__ __forceinline__ explicit CanvasOrder(const flexattn_mod_params& p) {
+        width = p.na_width;
+        layout = p.na_layout;
+        tile_log2 = p.na_tile > 0 ? 31 - __builtin_clz((unsigned)p.na_tile) : 0;
+        tiles_x = width >> tile_log2;
+        inv_width = fast_rcp((float)width);
+        inv_tiles_x = fast_rcp((float)tiles_x);
+    }
+    // n = quot * d + rem for 0 <= n < 2^24: a float estimate of the quotient (off by one at most),
+    // then one exact correction step
+    __device__ __forceinline__ static void divmod(int n, int d, float inv_d, int& quot, int& rem) {
+        int qq = (int)(((float)n + 0.5f) * inv_d);
+        int rr = n - qq * d;
+        const bool lo = rr < 0, hi = rr >= d;
+        quot = qq + (hi ? 1 : 0) - (lo ? 1 : 0);
+        rem = rr + (lo ? d : 0) - (hi ? d : 0);
+    }
+    // every second bit of v, packed (the inverse of interleaving with zeros)
+    __device__ __forceinline__ static int even_bits(uint32_t v) {
+        v &= 0x55555555u;
+        v = (v | (v >> 1)) & 0x33333333u;
+        v = (v | (v >> 2)) & 0x0f0f0f0fu;
+        v = (v | (v >> 4)) & 0x00ff00ffu;
+        v = (v | (v >> 8)) & 0x0000ffffu;
+        return (int)v;
+    }
+    __device__ __forceinline__ void pixel(int n, int& x, int& y) const {
+        if (layout == FLEXATTN_NA_MORTON) {
+            x = even_bits((uint32_t)n);
+            y = even_bits((uint32_t)n >> 1);
+        } else if (layout == FLEXATTN_NA_TILED) {
+            const int in_tile = n & ((1 << (2 * tile_log2)) - 1);
+            int ty, tx;
+            divmod(n >> (2 * tile_log2), tiles_x, inv_tiles_x, ty, tx);
+            y = (ty << tile_log2) + (in_tile >> tile_log2);
+            x = (tx << tile_log2) + (in_tile & ((1 << tile_log2) - 1));
+        } else {
+            divmod(n, width, inv_width, y, x);
+        }
+    }
+};
+
+struct NoCanvas {
+    __device__ __forceinline__ explicit NoCanvas(const flexattn_mod_params&) {}
+    __device__ __forceinline__ void pixel(int, int&, int&) const {}
+};
+
 template <uint32_t TERM>
 struct MaskTermRow {
     int q, window, prefix_len, doc_q, ctx;
     const int32_t* doc_row;
-    __device__ __forceinline__ MaskTermRow(const flexattn_mod_params& p, int b, int /*h*/, int q_idx) {
+    // NEIGHBORHOOD: the window of the query pixel, [x0, x0 + span] x [y0, y0 + span]
+    std::conditional_t<(TERM & FLEXATTN_M_NEIGHBORHOOD) != 0, CanvasOrder, NoCanvas> canvas;
+    int x0, y0, span;
+    __device__ __forceinline__ MaskTermRow(const flexattn_mod_params& p, int b, int /*h*/, int q_idx) : canvas(p) {
         q = q_idx;
         window = p.window;
         prefix_len = p.prefix_len;
         doc_row = nullptr;
         doc_q = 0;
         ctx = 0;
+        x0 = y0 = span = 0;
+        if constexpr (TERM & FLEXATTN_M_NEIGHBORHOOD) {
+            const int r = p.na_kernel >> 1;
+            int qx, qy;
+            canvas.pixel(q_idx, qx, qy);
+            x0 = min(max(qx, r), p.na_width - 1 - r) - r;
+            y0 = min(max(qy, r), p.na_height - 1 - r) - r;
+            span = 2 * r;
+        }
         if constexpr (TERM & FLEXATTN_M_DOCUMENT) {
             doc_row = p.doc_ids + (int64_t)b * p.doc_stride_b;
             doc_q = doc_row[q_idx];
@@ -99,6 +162,11 @@ struct MaskTermRow {
         if constexpr (TERM & FLEXATTN_M_DOCUMENT) r = r && (doc_row[kv] == doc_q);
         if constexpr (TERM & FLEXATTN_M_PREFIX) r = r && (kv < prefix_len);
         if constexpr (TERM & FLEXATTN_M_CTX_LEN) r = r && (kv < ctx);
+        if constexpr (TERM & FLEXATTN_M_NEIGHBORHOOD) {
+            int kx, ky;
+            canvas.pixel(kv, kx, ky);
+            r = r && ((unsigned)(kx - x0) <= (unsigned)span) && ((unsigned)(ky - y0) <= (unsigned)span);
+        }
         return r;
     }
 };
@@ -257,7 +325,7 @@ void set_last_hip_error(int e);
     } while (0)
 
 inline bool mask_id_valid(uint32_t m) {
-    return (m & ~0x1f1fu) == 0 && !((m & 0xffu) == 0 && (m >> 8) != 0);
+    return (m & ~0x3f3fu) == 0 && !((m & 0xffu) == 0 && (m >> 8) != 0);
 }
 inline bool score_id_valid(uint32_t s) { return (s & ~7u) == 0; }
 inline bool mask_uses(uint32_t m, uint32_t prim) { return ((m | (m >> 8)) & prim) != 0; }
@@ -274,7 +342,26 @@ inline int check_mod_params(uint32_t mask_id, uint32_t score_id, const flexattn_
     if ((score_id & FLEXATTN_SCORE_REL_BIAS) && (!p->rel_bias || p->rel_len <= 0 || p->rel_len > 1024))
         return FLEXATTN_ERR_INVALID_ARG;
     if ((score_id & FLEXATTN_SCORE_SOFTCAP) && !(p->softcap > 0.0f)) return FLEXATTN_ERR_INVALID_ARG;
+    if (mask_uses(mask_id, FLEXATTN_M_NEIGHBORHOOD)) {
+        const int w = p->na_width, h = p->na_height, k = p->na_kernel, t = p->na_tile;
+        if (w <= 0 || h <= 0 || (int64_t)w * h > (1 << 20)) return FLEXATTN_ERR_INVALID_ARG;
+        if (k < 1 || !(k & 1) || k > w || k > h) return FLEXATTN_ERR_INVALID_ARG;
+        if (p->na_layout == FLEXATTN_NA_TILED) {
+            if (t <= 0 || (t & (t - 1)) || w % t || h % t) return FLEXATTN_ERR_INVALID_ARG;
+        } else if (p->na_layout == FLEXATTN_NA_MORTON) {
+            if (w != h || (w & (w - 1))) return FLEXATTN_ERR_INVALID_ARG;
+        } else if (p->na_layout != FLEXATTN_NA_ROW_MAJOR) {
+            return FLEXATTN_ERR_INVALID_ARG;
+        }
+    }
     return FLEXATTN_OK;
+}
+
+// The neighborhood mask is defined on a canvas of exactly q_len == kv_len tokens.
+inline int check_canvas(uint32_t mask_id, const flexattn_mod_params* p, int q_len, int kv_len) {
+    if (!mask_uses(mask_id, FLEXATTN_M_NEIGHBORHOOD)) return FLEXATTN_OK;
+    const int64_t n = (int64_t)p->na_width * p->na_height;
+    return (q_len == n && kv_len == n) ? FLEXATTN_OK : FLEXATTN_ERR_INVALID_ARG;
 }
 
 // The (mask, score) pairs that forward/backward kernels are instantiated for.
@@ -288,6 +375,7 @@ inline int check_mod_params(uint32_t mask_id, uint32_t score_id, const flexattn_
     X(FLEXATTN_MASK_PREFIX_LM, FLEXATTN_SCORE_IDENTITY)                                 \
     X(FLEXATTN_MASK_DOCUMENT_CAUSAL, FLEXATTN_SCORE_IDENTITY)                           \
     X(FLEXATTN_MASK_DOCUMENT_CAUSAL, FLEXATTN_SCORE_ALIBI)                              \
-    X(FLEXATTN_MASK_SWA_CAUSAL_OR_PREFIX, FLEXATTN_SCORE_REL_BIAS)
+    X(FLEXATTN_MASK_SWA_CAUSAL_OR_PREFIX, FLEXATTN_SCORE_REL_BIAS)                      \
+    X(FLEXATTN_MASK_NEIGHBORHOOD, FLEXATTN_SCORE_IDENTITY)
 
 }  // namespace flexattn

@@ -5,18 +5,19 @@
 namespace flexattn {
 
 #define DECL(i) int fwd_launch_##i(const FwdArgs&, int, int, hipStream_t);
-DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8)
+DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8) DECL(9)
 #undef DECL
 typedef int (*FwdLauncher)(const FwdArgs&, int, int, hipStream_t);
 static const FwdLauncher kFwdLaunchers[kNumVariants] = {fwd_launch_0, fwd_launch_1, fwd_launch_2,
                                                         fwd_launch_3, fwd_launch_4, fwd_launch_5,
-                                                        fwd_launch_6, fwd_launch_7, fwd_launch_8};
+                                                        fwd_launch_6, fwd_launch_7, fwd_launch_8,
+                                                        fwd_launch_9};
 #define DECL(i) int fwd_paged_launch_##i(const FwdArgs&, int, int, hipStream_t);
-DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8)
+DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8) DECL(9)
 #undef DECL
 static const FwdLauncher kFwdPagedLaunchers[kNumVariants] = {
     fwd_paged_launch_0, fwd_paged_launch_1, fwd_paged_launch_2, fwd_paged_launch_3, fwd_paged_launch_4,
-    fwd_paged_launch_5, fwd_paged_launch_6, fwd_paged_launch_7, fwd_paged_launch_8};
+    fwd_paged_launch_5, fwd_paged_launch_6, fwd_paged_launch_7, fwd_paged_launch_8, fwd_paged_launch_9};
 
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(int e) { g_last_hip_error = e; }
@@ -80,6 +81,7 @@ extern "C" int flexattn_forward(const flexattn_dims* dims, const flexattn_tensor
     if ((rc = check_extent(K, dims->kv_len, dims->D)) || (rc = check_extent(V, dims->kv_len, dims->D))) return rc;
     if (!LSE || !(scale > 0.0f)) return FLEXATTN_ERR_INVALID_ARG;
     if ((rc = check_mod_params(mask_id, score_id, params)) != FLEXATTN_OK) return rc;
+    if ((rc = check_canvas(mask_id, params, dims->q_len, dims->kv_len)) != FLEXATTN_OK) return rc;
     const int vi = find_variant(mask_id, score_id);
     if (vi < 0) return FLEXATTN_ERR_UNSUPPORTED;
 
@@ -119,6 +121,7 @@ extern "C" int flexattn_paged_forward(const flexattn_dims* dims, const flexattn_
     if (page_size != bm->Bk) return FLEXATTN_ERR_UNSUPPORTED;     // a block of the BlockMask is a page
     if (bm->Bm != dims->B) return FLEXATTN_ERR_INVALID_ARG;        // every sequence has its own pages
     if ((rc = check_mod_params(mask_id, score_id, params)) != FLEXATTN_OK) return rc;
+    if ((rc = check_canvas(mask_id, params, dims->q_len, dims->kv_len)) != FLEXATTN_OK) return rc;
     const int vi = find_variant(mask_id, score_id);
     if (vi < 0) return FLEXATTN_ERR_UNSUPPORTED;
 

@@ -15,7 +15,7 @@ struct Variant {
 constexpr Variant kVariants[] = {FLEXATTN_FOR_EACH_VARIANT(FLEXATTN_VARIANT_ENTRY)};
 #undef FLEXATTN_VARIANT_ENTRY
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-static_assert(kNumVariants == 9, "update the launcher declarations in fwd.hip / bwd.hip and the build list");
+static_assert(kNumVariants == 10, "update the launcher declarations in fwd.hip / bwd.hip and the build list");
 
 inline int find_variant(uint32_t mask, uint32_t score) {
     for (int i = 0; i < kNumVariants; ++i)
