@@ -314,17 +314,20 @@ def flex_attention_backward(Q, K, V, dO, score_mod: ScoreMod, mask_mod: MaskMod,
 # --------------------------------------------------------------------------
 def block_kinds(mask_mod: MaskMod, Bm: int, Hm: int, q_len: int, kv_len: int, Bq: int, Bk: int):
     """Brute force: per block, count unmasked scalars.  Returns int8 [Bm,Hm,NR,NC]:
-    0 = skipped (all masked), 1 = partial, 2 = full (none masked); plus the total unmasked count."""
-    assert q_len % Bq == 0 and kv_len % Bk == 0
-    NR, NC = q_len // Bq, kv_len // Bk
+    0 = skipped (all masked), 1 = partial, 2 = full (none masked); plus the total unmasked count.
+    Lengths that are no multiple of the block size: NR and NC round up, and the part of a last
+    block that lies outside the score matrix counts as masked (such a block is never full)."""
+    NR, NC = -(-q_len // Bq), -(-kv_len // Bk)
     kinds = torch.zeros(Bm, Hm, NR, NC, dtype=torch.int8)
     pairs = 0
     kv_idx = _idx(0, kv_len).view(1, -1)
     for b in range(Bm):
         for h in range(Hm):
             for i in range(NR):
-                q_idx = _idx(i * Bq, (i + 1) * Bq).view(-1, 1)
-                keep = mask_mod(b, h, q_idx, kv_idx).expand(Bq, kv_len)
+                rows = min(Bq, q_len - i * Bq)
+                q_idx = _idx(i * Bq, i * Bq + rows).view(-1, 1)
+                keep = torch.zeros(Bq, NC * Bk, dtype=torch.bool)
+                keep[:rows, :kv_len] = mask_mod(b, h, q_idx, kv_idx).expand(rows, kv_len)
                 cnt = keep.reshape(Bq, NC, Bk).sum(dim=(0, 2))
                 pairs += int(cnt.sum())
                 kinds[b, h, i] = (cnt > 0).to(torch.int8) + (cnt == Bq * Bk).to(torch.int8)

@@ -118,6 +118,32 @@ def test_cfg4_counts_closed_form():
     assert int((kinds == 2).sum()) == n_full and int((kinds == 1).sum()) == n_part
 
 
+def test_ragged_lengths_round_up_and_the_outside_counts_as_masked():
+    # causal, q_len = kv_len = 200, 64 x 64 blocks: 4 x 4 blocks; the last row / column holds 8 tokens
+    S, B = 200, 64
+    kinds, pairs = fo.block_kinds(fo.causal_mask, 1, 1, S, S, B, B)
+    assert kinds.shape == (1, 1, 4, 4) and pairs == S * (S + 1) // 2
+    want = torch.tensor([[1, 0, 0, 0], [2, 1, 0, 0], [2, 2, 1, 0], [1, 1, 1, 1]], dtype=torch.int8)
+    assert torch.equal(kinds[0, 0], want)       # blocks of the last row are cut by the edge: never full
+    # no mask at all, 100 x 150 with 64 x 64 blocks: the inner block is full, the edge blocks partial
+    kinds, pairs = fo.block_kinds(fo.no_mask, 1, 1, 100, 150, 64, 64)
+    assert pairs == 100 * 150 and kinds[0, 0].tolist() == [[2, 2, 1], [1, 1, 1]]
+    # a multiple of the block size is unchanged by the rule, whatever lies beyond is simply absent
+    a, _ = fo.block_kinds(fo.causal_mask, 1, 1, 256, 256, 64, 64)
+    b, _ = fo.block_kinds(fo.causal_mask, 1, 1, 250, 250, 64, 64)
+    assert torch.equal(a[0, 0, :3, :3], b[0, 0, :3, :3]) and b[0, 0, 3].tolist() == [1, 1, 1, 1]
+    # scalar brute force on a tiny sliding-window case
+    mod = fo.and_mask(fo.causal_mask, fo.sliding_window_mask(3))
+    kinds, pairs = fo.block_kinds(mod, 1, 1, 10, 7, 4, 4)
+    for i in range(3):
+        for j in range(2):
+            cnt = sum(1 for q in range(4 * i, 4 * i + 4) for k in range(4 * j, 4 * j + 4)
+                      if q < 10 and k < 7 and k <= q and q - k <= 3)
+            assert int(kinds[0, 0, i, j]) == (0 if cnt == 0 else (2 if cnt == 16 else 1))
+    bm = fo.create_block_mask(mod, 1, 1, 10, 7, 4, 4)
+    assert bm["kv_indices"].shape == (1, 1, 3, 2) and bm["q_indices"].shape == (1, 1, 2, 3)
+
+
 def test_paged_conversion_and_phys2log():
     wl = wlm.CFG5.scaled(B=3, max_pages=8, page_size=4)
     inp = wlm.make_decode_inputs(wl, ctx_lens=[9, 32, 1], slack_pages=2)
