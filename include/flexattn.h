@@ -128,9 +128,11 @@ typedef struct flexattn_tensor {
 } flexattn_tensor;
 
 /* ---- BlockMask (section 4.2) -------------------------------------------------------
- * The score matrix is cut into Bq x Bk blocks: NR = q_len / Bq rows and NC = kv_len / Bk
- * columns of blocks.  A block with every scalar masked is skipped; one with none masked is
- * FULL (mask_mod is not evaluated in it); any other is PARTIAL.
+ * The score matrix is cut into Bq x Bk blocks: NR = ceil(q_len / Bq) rows and
+ * NC = ceil(kv_len / Bk) columns of blocks.  A block with every scalar masked is skipped; one
+ * with none masked is FULL (mask_mod is not evaluated in it); any other is PARTIAL.  Where a
+ * length is no multiple of the block size, the part of the last block that lies outside the
+ * score matrix counts as masked: such a block is PARTIAL or skipped, never FULL.
  *
  *   kv_num_blocks      [Bm, Hm, NR]      number of PARTIAL blocks in each row of blocks
  *   kv_indices         [Bm, Hm, NR, NC]  their column indices, ascending; entries past the
@@ -170,8 +172,7 @@ int flexattn_is_supported(uint32_t mask_id, uint32_t score_id, int32_t D);
 /* ---- BlockMask construction (section 4.2; create_block_mask, section 1.1) ----------
  * Evaluates mask_mod on every (q_idx, kv_idx) of every block -- brute force, so the result
  * is exact for any mask -- and fills the eight arrays of `bm` (both orientations).
- * Requires q_len % Bq == 0 and kv_len % Bk == 0 (otherwise FLEXATTN_ERR_UNSUPPORTED) and
- * Bq * Bk a multiple of 64.
+ * Any q_len, kv_len >= 1.
  *   stats  nullable device int64[4]: {#partial blocks, #full blocks, #blocks, #unmasked
  *          scalars}, summed over Bm * Hm.
  *   ws     device workspace of at least flexattn_blockmask_workspace_bytes() bytes.

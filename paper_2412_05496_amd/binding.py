@@ -232,7 +232,7 @@ def _dims(Q: torch.Tensor, K: torch.Tensor) -> _Dims:
 
 def alloc_blockmask(Bm: int, Hm: int, q_len: int, kv_len: int, Bq: int, Bk: int, device="cuda") -> BlockMask:
     """Caller-side allocation of the eight int32 arrays (the library allocates nothing)."""
-    NR, NC = q_len // Bq, kv_len // Bk
+    NR, NC = -(-q_len // Bq), -(-kv_len // Bk)       # the last block may be cut by the edge
     i32 = dict(dtype=torch.int32, device=device)
     return BlockMask(Bm, Hm, q_len, kv_len, Bq, Bk,
                      torch.empty(Bm, Hm, NR, **i32), torch.empty(Bm, Hm, NR, NC, **i32),

@@ -11,8 +11,8 @@ constexpr int kClassifyWaves = 4;
 
 template <uint32_t MASK>
 __global__ __launch_bounds__(kClassifyWaves * 64) void classify_blocks_kernel(
-    flexattn_mod_params p, int Bm, int Hm, int NR, int NC, int Bq, int Bk, uint8_t* __restrict__ kinds,
-    unsigned long long* __restrict__ stats) {
+    flexattn_mod_params p, int Bm, int Hm, int NR, int NC, int Bq, int Bk, int q_len, int kv_len,
+    uint8_t* __restrict__ kinds, unsigned long long* __restrict__ stats) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long long nblocks = (long long)Bm * Hm * NR * NC;
     const long long blk = (long long)blockIdx.x * kClassifyWaves + wave;
@@ -28,9 +28,10 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void classify_blocks_kernel(
         const int q_off = q_offset_of(p, b);
         int cnt = 0;
         for (int e = lane; e < n; e += 64) {
-            const int q = q_off + i * Bq + e / Bk, kv = j * Bk + e % Bk;
-            MaskRow<MASK> row(p, b, h, q);
-            cnt += row(kv) ? 1 : 0;
+            // rows and keys past the end of the score matrix count as masked
+            const int q = i * Bq + e / Bk, kv = j * Bk + e % Bk;
+            MaskRow<MASK> row(p, b, h, q_off + min(q, q_len - 1), kv_len);
+            cnt += (q < q_len && row(kv)) ? 1 : 0;
         }
         for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
         if (lane == 0) {
@@ -110,11 +111,11 @@ __global__ __launch_bounds__(256) void paged_convert_kernel(
 template <uint32_t MASK>
 static int launch_classify(const flexattn_mod_params& p, const flexattn_blockmask* bm, uint8_t* kinds,
                            unsigned long long* stats, hipStream_t st) {
-    const int NR = bm->q_len / bm->Bq, NC = bm->kv_len / bm->Bk;
+    const int NR = (bm->q_len + bm->Bq - 1) / bm->Bq, NC = (bm->kv_len + bm->Bk - 1) / bm->Bk;
     const long long nblocks = (long long)bm->Bm * bm->Hm * NR * NC;
     const long long grid = (nblocks + kClassifyWaves - 1) / kClassifyWaves;
     hipLaunchKernelGGL(classify_blocks_kernel<MASK>, dim3((unsigned)grid), dim3(kClassifyWaves * 64), 0, st, p,
-                       bm->Bm, bm->Hm, NR, NC, bm->Bq, bm->Bk, kinds, stats);
+                       bm->Bm, bm->Hm, NR, NC, bm->Bq, bm->Bk, bm->q_len, bm->kv_len, kinds, stats);
     return FLEXATTN_OK;
 }
 
@@ -125,7 +126,7 @@ using namespace flexattn;
 extern "C" size_t flexattn_blockmask_workspace_bytes(int32_t Bm, int32_t Hm, int32_t q_len, int32_t kv_len,
                                                      int32_t Bq, int32_t Bk) {
     if (Bm <= 0 || Hm <= 0 || q_len <= 0 || kv_len <= 0 || Bq <= 0 || Bk <= 0) return 0;
-    const size_t NR = (size_t)(q_len / Bq), NC = (size_t)(kv_len / Bk);
+    const size_t NR = ((size_t)q_len + Bq - 1) / Bq, NC = ((size_t)kv_len + Bk - 1) / Bk;
     return ((size_t)Bm * Hm * NR * NC + 255) & ~(size_t)255;
 }
 
@@ -141,8 +142,7 @@ extern "C" int flexattn_blockmask_build(uint32_t mask_id, const flexattn_mod_par
     int rc = check_mod_params(mask_id, 0, params);
     if (rc != FLEXATTN_OK) return rc;
     if ((rc = check_canvas(mask_id, params, bm->q_len, bm->kv_len)) != FLEXATTN_OK) return rc;
-    if (bm->q_len % bm->Bq != 0 || bm->kv_len % bm->Bk != 0) return FLEXATTN_ERR_UNSUPPORTED;
-    const int NR = bm->q_len / bm->Bq, NC = bm->kv_len / bm->Bk;
+    const int NR = (bm->q_len + bm->Bq - 1) / bm->Bq, NC = (bm->kv_len + bm->Bk - 1) / bm->Bk;
     const long long nblocks = (long long)bm->Bm * bm->Hm * NR * NC;
     if (nblocks > (1ll << 31) || (long long)bm->Bq * bm->Bk > (1ll << 24)) return FLEXATTN_ERR_UNSUPPORTED;
     if (ws_bytes < flexattn_blockmask_workspace_bytes(bm->Bm, bm->Hm, bm->q_len, bm->kv_len, bm->Bq, bm->Bk))

@@ -73,7 +73,8 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
     a.dv_sb = dV->stride_b; a.dv_sh = dV->stride_h; a.dv_ss = dV->stride_s;
     a.B = dims->B; a.Hq = dims->Hq; a.Hkv = dims->Hkv; a.G = dims->Hq / dims->Hkv;
     a.q_len = dims->q_len; a.kv_len = dims->kv_len;
-    a.NR = dims->q_len / bm->Bq; a.NC = dims->kv_len / bm->Bk; a.Bq = bm->Bq; a.Bk = bm->Bk;
+    a.NR = (dims->q_len + bm->Bq - 1) / bm->Bq; a.NC = (dims->kv_len + bm->Bk - 1) / bm->Bk;
+    a.Bq = bm->Bq; a.Bk = bm->Bk;
     a.bm_Bm = bm->Bm; a.bm_Hm = bm->Hm;
     a.kv_num = bm->kv_num_blocks; a.kv_idx = bm->kv_indices;
     a.full_kv_num = bm->full_kv_num_blocks; a.full_kv_idx = bm->full_kv_indices;

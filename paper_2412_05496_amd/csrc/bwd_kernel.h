@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
 
     // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
     const int units = a.B * a.Hkv;
-    const int tiles = a.kv_len / 64;
+    const int tiles = (a.kv_len + 63) / 64;
     const int id = blockIdx.x, xcd = id & 7, kk = id >> 3;
     const int unit = (kk / tiles) * 8 + xcd;
     if (unit >= units) return;
@@ -132,8 +132,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
     // K, V fragments of this wave's 32 keys: B operands (column = key, k-slots = dims)
     bf16x8 kf[NKS], vf[NKS];
     {
-        const bf16* kp = a.K + b * a.k_sb + hkv * a.k_sh + (int64_t)kv_lane * a.k_ss + half * 8;
-        const bf16* vp = a.V + b * a.v_sb + hkv * a.v_sh + (int64_t)kv_lane * a.v_ss + half * 8;
+        // keys past kv_len (last tile of a length that is no multiple of 64) take a copy of the last
+        // real key; the mask hides them and they are never stored
+        const int kv_ld = min(kv_lane, a.kv_len - 1);
+        const bf16* kp = a.K + b * a.k_sb + hkv * a.k_sh + (int64_t)kv_ld * a.k_ss + half * 8;
+        const bf16* vp = a.V + b * a.v_sb + hkv * a.v_sh + (int64_t)kv_ld * a.v_ss + half * 8;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             kf[ks] = *(const bf16x8*)(kp + ks * 16);
@@ -247,7 +250,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                 constexpr std::integral_constant<int, SLOT ^ 1> ld_slot{};
                 load_begin(ld_slot);
                 const bool partial = part_of[SLOT];
-                const int q_first = q_off + q0_of[SLOT] + 32 * x;   // as the mods see it
+                const int q_first = q0_of[SLOT] + 32 * x;
 
                 // scores
                 f32x4 nd[4], rcv4[4];
@@ -287,7 +290,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                         sv[i] = sacc[r];
                         rcv[i] = rcv4[r >> 2][r & 3];
                         // alibi / rel-bias need q - kv; the soft-cap and the plain score do not
-                        dqk[i] = (ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel) ? q_first + crow(r, half) - kv_lane : 0;
+                        dqk[i] = (ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel) ? q_off + q_first + crow(r, half) - kv_lane : 0;
                     }
                     smod.p_with_grad4(sv, dqk, rcv, gr, pe);
 #pragma unroll
@@ -296,7 +299,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
                         asm volatile("" ::: "memory");   // keep this a (scalar, rarely taken) branch
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            const MaskRow<MASK> mrow(a.p, b, hq, q_first + crow(4 * c4 + i, half));
+                            // (rows past q_len hold zeros in Q and dO: whatever the mask says there adds nothing)
+                            const MaskRow<MASK> mrow(a.p, b, hq, q_off + min(q_first + crow(4 * c4 + i, half), a.q_len - 1),
+                                                     a.kv_len);
                             const bool keep = mrow(kv_lane);
                             pe[i] = keep ? pe[i] : 0.0f;
                             ds[i] = keep ? ds[i] : 0.0f;
@@ -357,6 +362,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
         const float oscale = x ? a.scale * ScoreMod<SCORE>::grad_scale() : 1.0f;
         bf16* op = x ? a.dK + b * a.dk_sb + hkv * a.dk_sh + (int64_t)kv_lane * a.dk_ss
                      : a.dV + b * a.dv_sb + hkv * a.dv_sh + (int64_t)kv_lane * a.dv_ss;
+        if (kv_lane >= a.kv_len) return;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -397,29 +403,33 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     const int T = (n_full + n_part) * sub;
 
     bf16* dq_ptr = a.dQ + b * a.dq_sb + hq * a.dq_sh + (int64_t)q_row * a.dq_ss;
+    // rows past q_len are computed on a copy of the last real row and never stored
+    const bool real_row = q_row < a.q_len;
+    const int q_ld = min(q_row, a.q_len - 1);
     if (T == 0) {
-        for (int d0 = half * 8; d0 < D; d0 += 16) *(u32x4*)(dq_ptr + d0) = u32x4{0, 0, 0, 0};
+        if (real_row)
+            for (int d0 = half * 8; d0 < D; d0 += 16) *(u32x4*)(dq_ptr + d0) = u32x4{0, 0, 0, 0};
         return;
     }
 
     bf16x8 qf[D / 16], dof[D / 16];
     {
-        const bf16* qp = a.Q + b * a.q_sb + hq * a.q_sh + (int64_t)q_row * a.q_ss + half * 8;
-        const bf16* dp = a.dO + b * a.do_sb + hq * a.do_sh + (int64_t)q_row * a.do_ss + half * 8;
+        const bf16* qp = a.Q + b * a.q_sb + hq * a.q_sh + (int64_t)q_ld * a.q_ss + half * 8;
+        const bf16* dp = a.dO + b * a.do_sb + hq * a.do_sh + (int64_t)q_ld * a.do_ss + half * 8;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
             qf[ks] = *(const bf16x8*)(qp + ks * 16);
             dof[ks] = *(const bf16x8*)(dp + ks * 16);
         }
     }
-    const int64_t rowi = ((int64_t)b * a.Hq + hq) * a.q_len + q_row;
+    const int64_t rowi = ((int64_t)b * a.Hq + hq) * a.q_len + q_ld;
     const float lse2 = a.lse2[rowi], neg_delta = a.delta[rowi];
     const i32x4 k_rsrc = make_rsrc(a.K + b * a.k_sb + hkv * a.k_sh, (uint32_t)((a.kv_len - 1) * a.k_ss + D) * 2u);
     const i32x4 v_rsrc = make_rsrc(a.V + b * a.v_sb + hkv * a.v_sh, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
     const int k_row_bytes = (int)a.k_ss * 2, v_row_bytes = (int)a.v_ss * 2;
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
-    const int q_pos = q_row + q_offset_of(a.p, b);   // as the mods see it
-    const MaskRow<MASK> mrow(a.p, b, hq, q_pos);
+    const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
+    const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
 
     TileWalk<> walk(a.full_kv_idx + line * a.NC, a.kv_idx + line * a.NC, n_full, n_part, sub, a.Bk);
     const WaveTileLoader<D, NW> k_loader(a.k_ss, w, lane), v_loader(a.v_ss, w, lane);
@@ -540,6 +550,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     }
 
     const float qscale = a.scale * ScoreMod<SCORE>::grad_scale();
+    if (!real_row) return;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -554,7 +565,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
 template <uint32_t MASK, uint32_t SCORE>
 int launch_bwd_variant(const BwdArgs& a, int D, uint32_t stages, hipStream_t st) {
     const int units = a.B * a.Hkv;
-    const unsigned grid_kv = (unsigned)(((units + 7) / 8) * 8 * (a.kv_len / 64));
+    const unsigned grid_kv = (unsigned)(((units + 7) / 8) * 8 * ((a.kv_len + 63) / 64));
     const unsigned grid_q = (unsigned)(((units + 7) / 8) * 8 * a.G * a.NR);
     const bool kv = stages & FLEXATTN_BWD_DKDV, q = stages & FLEXATTN_BWD_DQ;
     if (stages & FLEXATTN_BWD_DELTA) {

@@ -182,12 +182,17 @@ struct MaskRow {
     static constexpr uint32_t T0 = MASK & 0xffu, T1 = (MASK >> 8) & 0xffu;
     MaskTermRow<T0> t0;
     MaskTermRow<T1> t1;
-    __device__ __forceinline__ MaskRow(const flexattn_mod_params& p, int b, int h, int q_idx)
-        : t0(p, b, h, q_idx), t1(p, b, h, q_idx) {}
+    int kv_last;
+    // kv_len: keys at or past it do not exist (last block of a length that is no multiple of the
+    // block size): they are masked, and the primitives are evaluated at the last real key instead
+    // so that no table is read out of range.  q_idx must be a real row.
+    __device__ __forceinline__ MaskRow(const flexattn_mod_params& p, int b, int h, int q_idx, int kv_len)
+        : t0(p, b, h, q_idx), t1(p, b, h, q_idx), kv_last(kv_len - 1) {}
     __device__ __forceinline__ bool operator()(int kv) const {
-        bool r = t0(kv);
-        if constexpr (T1 != 0) r = r || t1(kv);
-        return r;
+        const int kc = min(kv, kv_last);
+        bool r = t0(kc);
+        if constexpr (T1 != 0) r = r || t1(kc);
+        return r && kv <= kv_last;
     }
 };
 

@@ -45,7 +45,6 @@ int check_problem(const flexattn_dims* d, const flexattn_blockmask* bm) {
     if (bm->q_len != d->q_len || bm->kv_len != d->kv_len) return FLEXATTN_ERR_INVALID_ARG;
     if (!(bm->Bm == 1 || bm->Bm == d->B) || !(bm->Hm == 1 || bm->Hm == d->Hq)) return FLEXATTN_ERR_INVALID_ARG;
     if (!(bm->Bq == 64 || bm->Bq == 128) || !(bm->Bk == 64 || bm->Bk == 128)) return FLEXATTN_ERR_UNSUPPORTED;
-    if (d->q_len % bm->Bq != 0 || d->kv_len % bm->Bk != 0) return FLEXATTN_ERR_UNSUPPORTED;
     if (!bm->kv_num_blocks || !bm->kv_indices || !bm->full_kv_num_blocks || !bm->full_kv_indices)
         return FLEXATTN_ERR_INVALID_ARG;
     return FLEXATTN_OK;
@@ -94,7 +93,8 @@ extern "C" int flexattn_forward(const flexattn_dims* dims, const flexattn_tensor
     a.o_sb = O->stride_b; a.o_sh = O->stride_h; a.o_ss = O->stride_s;
     a.B = dims->B; a.Hq = dims->Hq; a.Hkv = dims->Hkv; a.G = dims->Hq / dims->Hkv;
     a.q_len = dims->q_len; a.kv_len = dims->kv_len;
-    a.NR = dims->q_len / bm->Bq; a.NC = dims->kv_len / bm->Bk; a.Bk = bm->Bk; a.sub = bm->Bk / kTileKV;
+    a.NR = (dims->q_len + bm->Bq - 1) / bm->Bq; a.NC = (dims->kv_len + bm->Bk - 1) / bm->Bk;
+    a.Bk = bm->Bk; a.sub = bm->Bk / kTileKV;
     a.bm_Bm = bm->Bm; a.bm_Hm = bm->Hm;
     a.kv_num = bm->kv_num_blocks; a.kv_idx = bm->kv_indices;
     a.full_num = bm->full_kv_num_blocks; a.full_idx = bm->full_kv_indices;
@@ -134,7 +134,8 @@ extern "C" int flexattn_paged_forward(const flexattn_dims* dims, const flexattn_
     a.o_sb = O->stride_b; a.o_sh = O->stride_h; a.o_ss = O->stride_s;
     a.B = dims->B; a.Hq = dims->Hq; a.Hkv = dims->Hkv; a.G = dims->Hq / dims->Hkv;
     a.q_len = dims->q_len; a.kv_len = dims->kv_len;
-    a.NR = dims->q_len / bm->Bq; a.NC = dims->kv_len / bm->Bk; a.Bk = bm->Bk; a.sub = bm->Bk / kTileKV;
+    a.NR = (dims->q_len + bm->Bq - 1) / bm->Bq; a.NC = (dims->kv_len + bm->Bk - 1) / bm->Bk;
+    a.Bk = bm->Bk; a.sub = bm->Bk / kTileKV;
     a.bm_Bm = bm->Bm; a.bm_Hm = bm->Hm;
     a.kv_num = bm->kv_num_blocks; a.kv_idx = bm->kv_indices;
     a.full_num = bm->full_kv_num_blocks; a.full_idx = bm->full_kv_indices;

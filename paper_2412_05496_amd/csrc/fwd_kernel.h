@@ -85,16 +85,22 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
 
     bf16* o_ptr = a.O + b * a.o_sb + hq * a.o_sh + (int64_t)q_row * a.o_ss;
     float* lse_ptr = a.LSE + ((int64_t)b * a.Hq + hq) * a.q_len + q_row;
+    // rows past q_len (last block of a length that is no multiple of Bq) are computed on a copy of
+    // the last real row and never stored
+    const bool real_row = q_row < a.q_len;
+    const int q_ld = min(q_row, a.q_len - 1);
     if (T == 0) {   // every key of these rows is masked
-        for (int d0 = half * 8; d0 < D; d0 += 16) *(u32x4*)(o_ptr + d0) = u32x4{0, 0, 0, 0};
-        if (half == 0) *lse_ptr = -INFINITY;
+        if (real_row) {
+            for (int d0 = half * 8; d0 < D; d0 += 16) *(u32x4*)(o_ptr + d0) = u32x4{0, 0, 0, 0};
+            if (half == 0) *lse_ptr = -INFINITY;
+        }
         return;
     }
 
     // Q fragments: B operand of K Q^T, column q_row, k-slots d = 16 ks + 8 half + [0, 8)
     bf16x8 qf[D / 16];
     {
-        const bf16* qp = a.Q + b * a.q_sb + hq * a.q_sh + (int64_t)q_row * a.q_ss + half * 8;
+        const bf16* qp = a.Q + b * a.q_sb + hq * a.q_sh + (int64_t)q_ld * a.q_ss + half * 8;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *(const bf16x8*)(qp + ks * 16);
     }
@@ -120,8 +126,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     };
 
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
-    const int q_pos = q_row + q_offset_of(a.p, b);   // as the mods see it
-    const MaskRow<MASK> mrow(a.p, b, hq, q_pos);
+    const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
+    const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
     const float inv_neg2c = smod.capl2 > 0.0f ? -0.5f / smod.capl2 : 0.0f;   // 1 / (-2 cap log2 e)
 
     // first key and PARTIAL flag of tiles t, t+1, t+2 (the walk is always two tiles ahead)
@@ -324,6 +330,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
     // ---- epilogue: O = O^T / l, LSE = ln 2 * (m + log2 l)
     const float l_tot = l_run + swap_halves(l_run);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+    if (!real_row) return;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll

@@ -71,12 +71,12 @@ def test_null_and_bad_arguments_are_rejected_on_the_host():
     bm1 = binding._BlockMask(1, 1, 128, 256, 128, 64, 1, 1, 1, 1, 1, 1, 1, 1)
     args1 = (0, 0, None, C.byref(bm1), 16, 16, 1.0, C.byref(t), 16, None)
     assert lib.flexattn_paged_forward(C.byref(d), C.byref(t), 16, 16, 64, 8, *args1) == fa.ERR_INVALID_ARG
-    # ragged sequence (q_len % Bq != 0) is refused by the builder
+    # a mask without its parameters is refused; lengths need not be multiples of the block size
     bm = binding._BlockMask(1, 1, 100, 128, 64, 64, 1, 1, 1, 1, 1, 1, 1, 1)
     assert lib.flexattn_blockmask_build(fa.MASK_CAUSAL, None, C.byref(bm), None, 1, 1 << 20, None) == fa.ERR_INVALID_ARG
     p = binding._ModParams()
-    assert lib.flexattn_blockmask_build(fa.MASK_CAUSAL, C.byref(p), C.byref(bm), None, 1, 1 << 20,
-                                        None) == fa.ERR_UNSUPPORTED
+    assert lib.flexattn_blockmask_build(fa.MASK_CAUSAL, C.byref(p), C.byref(bm), None, 1, 1, None) == fa.ERR_WORKSPACE
+    assert fa.flexattn_blockmask_workspace_bytes(1, 1, 100, 129, 64, 64) >= 2 * 3
     # document mask without doc_ids
     bm = binding._BlockMask(1, 1, 128, 128, 64, 64, 1, 1, 1, 1, 1, 1, 1, 1)
     assert lib.flexattn_blockmask_build(fa.MASK_DOCUMENT, C.byref(p), C.byref(bm), None, 1, 1 << 20,
