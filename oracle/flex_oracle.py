@@ -31,6 +31,10 @@ What follows what (paper = arXiv 2412.05496):
 * ``neighborhood_mask``         appendix (Neighborhood Attention): every pixel of a 2-D canvas attends
                                 to its K x K nearest pixels; the tokens are laid out row by row,
                                 in 2-D tiles, or along the Morton curve.
+* ``flex_attention_backward_captured``  gradients of the tensors a score_mod captures (the bias of
+                                the ALiBi example, the table of the relative-bias example,
+                                section 3.1): chain rule through the mods, pinned by finite
+                                differences and library autograd in the tests.
 * ``flex_attention_backward``   the paper only states that a backward template
                                 exists (section 4.1); this is ordinary calculus on
                                 Eq. 1, pinned by finite differences in the tests.
@@ -127,6 +131,10 @@ class ScoreMod:
         """d score_mod / d score evaluated at `score` (same shape)."""
         raise NotImplementedError
 
+    def captured_grad(self, score, b, h, q_idx, kv_idx, g_out, out: dict):
+        """Adds to out[name] the gradient of the tensors this mod captures, given g_out = dL / d(this
+        mod's output) (same shape as score).  Mods that capture no tensor add nothing."""
+
 
 class Identity(ScoreMod):
     def __call__(self, score, b, h, q_idx, kv_idx):
@@ -147,6 +155,10 @@ class Alibi(ScoreMod):
 
     def grad(self, score, b, h, q_idx, kv_idx):
         return torch.ones_like(score)
+
+    def captured_grad(self, score, b, h, q_idx, kv_idx, g_out, out):
+        d = out.setdefault("alibi_bias", torch.zeros_like(self.bias))
+        d[h] += (g_out * (q_idx - kv_idx).to(F64)).sum()
 
 
 class Softcap(ScoreMod):
@@ -176,6 +188,11 @@ class RelBias(ScoreMod):
     def grad(self, score, b, h, q_idx, kv_idx):
         return torch.ones_like(score)
 
+    def captured_grad(self, score, b, h, q_idx, kv_idx, g_out, out):
+        d = out.setdefault("rel_bias", torch.zeros_like(self.table))
+        rel = (q_idx - kv_idx).clamp(0, self.table.shape[1] - 1).expand_as(g_out)
+        d[h].index_add_(0, rel.reshape(-1), g_out.reshape(-1))
+
 
 class Compose(ScoreMod):
     """Nested score_mods: outer(inner(score))."""
@@ -189,6 +206,11 @@ class Compose(ScoreMod):
     def grad(self, score, b, h, q_idx, kv_idx):
         mid = self.inner(score, b, h, q_idx, kv_idx)
         return self.outer.grad(mid, b, h, q_idx, kv_idx) * self.inner.grad(score, b, h, q_idx, kv_idx)
+
+    def captured_grad(self, score, b, h, q_idx, kv_idx, g_out, out):
+        mid = self.inner(score, b, h, q_idx, kv_idx)
+        self.outer.captured_grad(mid, b, h, q_idx, kv_idx, g_out, out)
+        self.inner.captured_grad(score, b, h, q_idx, kv_idx, g_out * self.outer.grad(mid, b, h, q_idx, kv_idx), out)
 
 
 # --------------------------------------------------------------------------
@@ -307,6 +329,31 @@ def flex_attention_backward(Q, K, V, dO, score_mod: ScoreMod, mask_mod: MaskMod,
             dK[b, h // G] += dk
             dV[b, h // G] += dv
     return dQ, dK, dV
+
+
+def flex_attention_backward_captured(Q, K, V, dO, score_mod: ScoreMod, mask_mod: MaskMod,
+                                     scale: Optional[float] = None, stripe: int = 1024) -> dict:
+    """Gradients of the tensors the score_mod captures (ALiBi bias per head, relative-bias table;
+    section 3.1 examples), summed over batch and positions: {name: tensor like the captured one}.
+    With dS' = P * (dP - delta) the gradient flowing into the score_mod's output (zero where masked),
+    every mod passes it on to what it captures (chain rule through the mods applied after it)."""
+    B, Hq, Sq, D = Q.shape
+    G = Hq // K.shape[1]
+    scale = 1.0 / math.sqrt(D) if scale is None else scale
+    out: dict = {}
+    kv_idx = _idx(0, K.shape[2]).view(1, -1)
+    for b in range(B):
+        for h in range(Hq):
+            Qh, Kh, Vh, dOh = (t.to(F64) for t in (Q[b, h], K[b, h // G], V[b, h // G], dO[b, h]))
+            for r0 in range(0, Sq, stripe):
+                q_idx = _idx(r0, min(r0 + stripe, Sq))
+                s, s_mod, keep = _modified_scores(Qh, Kh, score_mod, mask_mod, scale, b, h, q_idx)
+                P, _ = _softmax_rows(s_mod, keep)
+                dP = dOh[q_idx] @ Vh.T
+                delta = (P * dP).sum(dim=1, keepdim=True)
+                g_out = torch.where(keep, P * (dP - delta), torch.zeros_like(P))
+                score_mod.captured_grad(s, b, h, q_idx.view(-1, 1), kv_idx, g_out, out)
+    return out
 
 
 # --------------------------------------------------------------------------
@@ -453,6 +500,9 @@ class QOffset(ScoreMod):
 
     def grad(self, score, b, h, q_idx, kv_idx):
         return self.inner.grad(score, b, h, q_idx + self.off[b], kv_idx)
+
+    def captured_grad(self, score, b, h, q_idx, kv_idx, g_out, out):
+        self.inner.captured_grad(score, b, h, q_idx + self.off[b], kv_idx, g_out, out)
 
 
 def paged_attention(Q, K_pool, V_pool, page_table, kv_lens, q_offsets, score_mod: ScoreMod, mask_mod: MaskMod,
