@@ -201,7 +201,7 @@ int flexattn_forward(const flexattn_dims* dims,
  *   dV = P^T dO;  dP = dO V^T;  dS' = P * (dP - rowsum(dO * O));  dS = dS' * d score_mod/d s;
  *   dQ = scale * dS K;  dK = scale * dS^T Q;  dK and dV are summed over the Hq / Hkv query
  * heads that share a KV head.  Gradients with respect to captured buffers (alibi_bias,
- * rel_bias) are not produced.  dQ [B,Hq,q_len,D], dK, dV [B,Hkv,kv_len,D] bf16.
+ * rel_bias) come from flexattn_backward_captured.  dQ [B,Hq,q_len,D], dK, dV [B,Hkv,kv_len,D] bf16.
  *   ws     device workspace of at least flexattn_backward_workspace_bytes(dims) bytes.
  */
 size_t flexattn_backward_workspace_bytes(const flexattn_dims* dims);
@@ -230,6 +230,27 @@ int flexattn_backward_stages(const flexattn_dims* dims,
                              const flexattn_blockmask* bm, float scale,
                              const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
                              void* ws, size_t ws_bytes, void* stream, uint32_t stages);
+
+/* Gradients of the tensors the score_mod captures (the bias of the ALiBi example, the table of the
+ * relative-bias example, section 3.1), which flexattn_backward does not produce:
+ *   d_alibi_bias [Hq] fp32          sum over b, q, kv of dS * (q_idx - kv_idx)
+ *   d_rel_bias   [Hq, rel_len] fp32 sum of dS over the pairs that read each table entry
+ * with dS the gradient of the loss with respect to the biased score (before a soft-cap that
+ * follows it).  Each is written (not accumulated) if the score_id selects its mod and must then
+ * be non-NULL; FLEXATTN_ERR_UNSUPPORTED if the score_mod captures nothing.  Arguments as in
+ * flexattn_backward (O and LSE from the forward); ws of at least
+ * flexattn_backward_captured_workspace_bytes() bytes.  The sums over one workgroup's pairs use
+ * LDS atomics, so the last bits can differ between runs; the sum over workgroups has a fixed order.
+ */
+size_t flexattn_backward_captured_workspace_bytes(const flexattn_dims* dims, const flexattn_blockmask* bm,
+                                                  uint32_t score_id, const flexattn_mod_params* params);
+int flexattn_backward_captured(const flexattn_dims* dims,
+                               const flexattn_tensor* Q, const flexattn_tensor* K, const flexattn_tensor* V,
+                               const flexattn_tensor* O, const flexattn_tensor* dO, const float* LSE,
+                               uint32_t score_id, uint32_t mask_id, const flexattn_mod_params* params,
+                               const flexattn_blockmask* bm, float scale,
+                               float* d_alibi_bias, float* d_rel_bias,
+                               void* ws, size_t ws_bytes, void* stream);
 
 /* ---- paged attention (section 5.1) --------------------------------------------------
  * BlockMask conversion: each of the first num_blocks[b,h,i] entries j of indices[b,h,i,:]

@@ -120,6 +120,12 @@ def _lib():
                                       P(_Tensor), P(_Tensor), P(_Tensor), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.flexattn_backward_stages.restype = C.c_int
     lib.flexattn_backward_stages.argtypes = lib.flexattn_backward.argtypes + [C.c_uint32]
+    lib.flexattn_backward_captured_workspace_bytes.restype = C.c_size_t
+    lib.flexattn_backward_captured_workspace_bytes.argtypes = [P(_Dims), P(_BlockMask), C.c_uint32, P(_ModParams)]
+    lib.flexattn_backward_captured.restype = C.c_int
+    lib.flexattn_backward_captured.argtypes = [P(_Dims), P(_Tensor), P(_Tensor), P(_Tensor), P(_Tensor), P(_Tensor),
+                                               C.c_void_p, C.c_uint32, C.c_uint32, P(_ModParams), P(_BlockMask),
+                                               C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.flexattn_paged_convert_blockmask.restype = C.c_int
     lib.flexattn_paged_convert_blockmask.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                                      C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -322,6 +328,24 @@ def flexattn_backward_stages(Q, K, V, O, dO, LSE, score_id: int, mask_id: int, p
                                            *(None if t is None else C.byref(t) for t in outs),
                                            ws.data_ptr(), ws.numel(), _stream(), stages), "flexattn_backward_stages")
     return dQ, dK, dV
+
+
+def flexattn_backward_captured(Q, K, V, O, dO, LSE, score_id: int, mask_id: int, params: ModParams, bm: BlockMask,
+                               scale: float, d_alibi_bias: Optional[torch.Tensor] = None,
+                               d_rel_bias: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """Gradients of the captured alibi_bias [Hq] / rel_bias [Hq, rel_len] (fp32, written)."""
+    for t in (d_alibi_bias, d_rel_bias):
+        assert t is None or (t.dtype == torch.float32 and t.is_cuda and t.is_contiguous())
+    d, p, c = _dims(Q, K), params._c(), bm._c()
+    if ws is None:
+        n = _lib().flexattn_backward_captured_workspace_bytes(C.byref(d), C.byref(c), score_id, C.byref(p))
+        ws = torch.empty(max(n, 1), dtype=torch.uint8, device=Q.device)
+    ts = [_tensor(t) for t in (Q, K, V, O, dO)]
+    _check(_lib().flexattn_backward_captured(C.byref(d), *(C.byref(t) for t in ts), LSE.data_ptr(), score_id, mask_id,
+                                             C.byref(p), C.byref(c), scale, _ptr(d_alibi_bias), _ptr(d_rel_bias),
+                                             ws.data_ptr(), ws.numel(), _stream()),
+           "flexattn_backward_captured")
+    return d_alibi_bias, d_rel_bias
 
 
 def flexattn_paged_convert_blockmask(num_blocks, indices, page_table, phys_indices, phys2log=None):

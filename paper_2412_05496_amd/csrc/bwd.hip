@@ -101,3 +101,94 @@ extern "C" int flexattn_backward(const flexattn_dims* dims, const flexattn_tenso
     return flexattn_backward_stages(dims, Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, scale, dQ, dK, dV, ws,
                                     ws_bytes, stream, FLEXATTN_BWD_ALL);
 }
+
+// ---- gradients of captured tensors -----------------------------------------------------------
+namespace {
+// Sum of the per-workgroup partials over batch and rows of blocks, in a fixed order, times `factor`:
+// out[hq, i] = factor * sum_{b, row} part[((b * Hq + hq) * NR + row) * width + i].
+__global__ __launch_bounds__(256) void captured_reduce_kernel(const float* __restrict__ part, int B, int Hq, int NR,
+                                                              int width, float factor, float* __restrict__ out) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= Hq * width) return;
+    const int hq = idx / width, i = idx - hq * width;
+    double sum = 0.0;
+    for (int b = 0; b < B; ++b)
+        for (int row = 0; row < NR; ++row) sum += (double)part[(((int64_t)b * Hq + hq) * NR + row) * width + i];
+    out[idx] = (float)(sum * (double)factor);
+}
+
+size_t captured_rows(const flexattn_dims* d) { return (size_t)d->B * d->Hq * d->q_len; }
+size_t captured_slots(const flexattn_dims* d, const flexattn_blockmask* bm) {
+    return (size_t)d->B * d->Hq * ((d->q_len + bm->Bq - 1) / bm->Bq);
+}
+}  // namespace
+
+extern "C" size_t flexattn_backward_captured_workspace_bytes(const flexattn_dims* d, const flexattn_blockmask* bm,
+                                                             uint32_t score_id, const flexattn_mod_params* params) {
+    if (!d || !bm || d->B <= 0 || d->Hq <= 0 || d->q_len <= 0 || bm->Bq <= 0) return 0;
+    size_t n = 2 * captured_rows(d);                                   // -delta and the row constants
+    if (score_id & FLEXATTN_SCORE_ALIBI) n += captured_slots(d, bm);
+    if ((score_id & FLEXATTN_SCORE_REL_BIAS) && params && params->rel_len > 0)
+        n += captured_slots(d, bm) * (size_t)params->rel_len;
+    return n * sizeof(float);
+}
+
+extern "C" int flexattn_backward_captured(const flexattn_dims* dims, const flexattn_tensor* Q,
+                                          const flexattn_tensor* K, const flexattn_tensor* V, const flexattn_tensor* O,
+                                          const flexattn_tensor* dO, const float* LSE, uint32_t score_id,
+                                          uint32_t mask_id, const flexattn_mod_params* params,
+                                          const flexattn_blockmask* bm, float scale, float* d_alibi_bias,
+                                          float* d_rel_bias, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_problem(dims, bm);
+    if (rc != FLEXATTN_OK) return rc;
+    const flexattn_tensor* ts[] = {Q, K, V, O, dO};
+    for (const flexattn_tensor* t : ts)
+        if ((rc = check_tensor(t)) != FLEXATTN_OK) return rc;
+    if ((rc = check_extent(K, dims->kv_len, dims->D)) != FLEXATTN_OK) return rc;
+    if ((rc = check_extent(V, dims->kv_len, dims->D)) != FLEXATTN_OK) return rc;
+    if (!LSE || !ws || !(scale > 0.0f) || ((uintptr_t)ws & 15)) return FLEXATTN_ERR_INVALID_ARG;
+    if ((rc = check_mod_params(mask_id, score_id, params)) != FLEXATTN_OK) return rc;
+    if ((rc = check_canvas(mask_id, params, dims->q_len, dims->kv_len)) != FLEXATTN_OK) return rc;
+    const bool alibi = score_id & FLEXATTN_SCORE_ALIBI, rel = score_id & FLEXATTN_SCORE_REL_BIAS;
+    if (!alibi && !rel) return FLEXATTN_ERR_UNSUPPORTED;               // nothing is captured
+    if ((alibi && !d_alibi_bias) || (rel && !d_rel_bias)) return FLEXATTN_ERR_INVALID_ARG;
+    const int vi = find_variant(mask_id, score_id);
+    if (vi < 0) return FLEXATTN_ERR_UNSUPPORTED;
+    if (ws_bytes < flexattn_backward_captured_workspace_bytes(dims, bm, score_id, params)) return FLEXATTN_ERR_WORKSPACE;
+
+    BwdArgs a = {};
+    a.Q = (const bf16*)Q->ptr; a.K = (const bf16*)K->ptr; a.V = (const bf16*)V->ptr;
+    a.O = (const bf16*)O->ptr; a.dO = (const bf16*)dO->ptr; a.LSE = LSE;
+    const size_t rows = captured_rows(dims), slots = captured_slots(dims, bm);
+    a.delta = (float*)ws; a.lse2 = (float*)ws + rows;
+    a.cap_alibi = (float*)ws + 2 * rows;
+    a.cap_rel = a.cap_alibi + (alibi ? slots : 0);
+    a.q_sb = Q->stride_b; a.q_sh = Q->stride_h; a.q_ss = Q->stride_s;
+    a.k_sb = K->stride_b; a.k_sh = K->stride_h; a.k_ss = K->stride_s;
+    a.v_sb = V->stride_b; a.v_sh = V->stride_h; a.v_ss = V->stride_s;
+    a.o_sb = O->stride_b; a.o_sh = O->stride_h; a.o_ss = O->stride_s;
+    a.do_sb = dO->stride_b; a.do_sh = dO->stride_h; a.do_ss = dO->stride_s;
+    a.B = dims->B; a.Hq = dims->Hq; a.Hkv = dims->Hkv; a.G = dims->Hq / dims->Hkv;
+    a.q_len = dims->q_len; a.kv_len = dims->kv_len;
+    a.NR = (dims->q_len + bm->Bq - 1) / bm->Bq; a.NC = (dims->kv_len + bm->Bk - 1) / bm->Bk;
+    a.Bq = bm->Bq; a.Bk = bm->Bk;
+    a.bm_Bm = bm->Bm; a.bm_Hm = bm->Hm;
+    a.kv_num = bm->kv_num_blocks; a.kv_idx = bm->kv_indices;
+    a.full_kv_num = bm->full_kv_num_blocks; a.full_kv_idx = bm->full_kv_indices;
+    a.scale = scale;
+    a.p = *params;
+
+    hipStream_t st = (hipStream_t)stream;
+    rc = kBwdLaunchers[vi](a, dims->D, FLEXATTN_BWD_DELTA | kBwdStageCaptured, st);
+    if (rc != FLEXATTN_OK) return rc;
+    // the kernels' dS lacks the constant factor of the score_mod's derivative
+    const float factor = (score_id & FLEXATTN_SCORE_SOFTCAP) ? 4.0f : 1.0f;
+    if (alibi)
+        hipLaunchKernelGGL(captured_reduce_kernel, dim3((unsigned)((a.Hq + 255) / 256)), dim3(256), 0, st, a.cap_alibi,
+                           a.B, a.Hq, a.NR, 1, factor, d_alibi_bias);
+    if (rel)
+        hipLaunchKernelGGL(captured_reduce_kernel, dim3((unsigned)((a.Hq * a.p.rel_len + 255) / 256)), dim3(256), 0, st,
+                           a.cap_rel, a.B, a.Hq, a.NR, a.p.rel_len, factor, d_rel_bias);
+    FLEXATTN_HIP_TRY(hipGetLastError());
+    return FLEXATTN_OK;
+}

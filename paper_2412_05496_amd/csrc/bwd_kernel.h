@@ -37,6 +37,9 @@ struct BwdArgs {
     bf16* dV;
     float* delta;   // [B, Hq, q_len]  MINUS rowsum(dO * O): the dP accumulators start from it
     float* lse2;    // [B, Hq, q_len]  row constant rc of ScoreMod::p_with_grad (from LSE); -inf for dead rows
+    // gradients of captured tensors: per-workgroup partial sums, [B, Hq, NR] and [B, Hq, NR, rel_len]
+    float* cap_alibi;
+    float* cap_rel;
     int64_t q_sb, q_sh, q_ss, k_sb, k_sh, k_ss, v_sb, v_sh, v_ss, o_sb, o_sh, o_ss, do_sb, do_sh, do_ss;
     int64_t dq_sb, dq_sh, dq_ss, dk_sb, dk_sh, dk_ss, dv_sb, dv_sh, dv_ss;
     int B, Hq, Hkv, G, q_len, kv_len;
@@ -377,11 +380,18 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
 
 // ------------------------------------------------------------------------------------------
 // dQ.  NW waves, each owning 32 query rows of the row of blocks; structure of the forward kernel.
-template <int D, int NW, uint32_t MASK, uint32_t SCORE>
+// CAPTURED: the same walk and the same dS, but instead of dQ the kernel sums what the score_mod's
+// captured tensors receive: dS * (q_idx - kv_idx) for the ALiBi bias of the head, dS per table entry
+// for the relative bias (the factor ScoreMod::grad_scale() is applied by the reduction that follows).
+// One partial result per workgroup; the blocks whose every pair falls on the table's last (or first)
+// entry are summed in registers, the others entry by entry with LDS atomics.
+template <int D, int NW, uint32_t MASK, uint32_t SCORE, bool CAPTURED = false>
 __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     constexpr int Bq = NW * 32;
     constexpr int TILE = 64 * D;
     __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];   // K(even), K(odd), V(even), V(odd)
+    constexpr int kTabAlibi = 1024;                                  // the table has at most 1024 entries
+    __shared__ float s_tab[CAPTURED ? kTabAlibi + 1 : 1];            // relative-bias entries, then the ALiBi sum
 
     const int units = a.B * a.Hkv;
     const int id = blockIdx.x, xcd = id & 7, kk = id >> 3;
@@ -406,11 +416,20 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     // rows past q_len are computed on a copy of the last real row and never stored
     const bool real_row = q_row < a.q_len;
     const int q_ld = min(q_row, a.q_len - 1);
+    const int64_t cap_slot = ((int64_t)b * a.Hq + hq) * a.NR + row;
     if (T == 0) {
-        if (real_row)
+        if constexpr (CAPTURED) {
+            if constexpr (ScoreMod<SCORE>::kRel)
+                for (int i = tid; i < a.p.rel_len; i += NW * 64) a.cap_rel[cap_slot * a.p.rel_len + i] = 0.0f;
+            if constexpr (ScoreMod<SCORE>::kAlibi)
+                if (tid == 0) a.cap_alibi[cap_slot] = 0.0f;
+        } else if (real_row) {
             for (int d0 = half * 8; d0 < D; d0 += 16) *(u32x4*)(dq_ptr + d0) = u32x4{0, 0, 0, 0};
+        }
         return;
     }
+    if constexpr (CAPTURED)
+        for (int i = tid; i <= kTabAlibi; i += NW * 64) s_tab[i] = 0.0f;   // before the first barrier below
 
     bf16x8 qf[D / 16], dof[D / 16];
     {
@@ -439,7 +458,10 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     };
     const RowReader<D> row_reader(l32, half, lds_addr(smem));
     const TrReader<D> tr_reader(lane, lds_addr(smem));
-    const float rc = lse2;                     // the delta kernel stored the row constant
+    // the delta kernel stored the row constant; a row past q_len must add nothing to the sums
+    const float rc = (CAPTURED && !real_row) ? -INFINITY : lse2;
+    const int q_wave_min = row * Bq + w * 32 + q_offset_of(a.p, b);   // smallest q_idx of this wave's rows
+    float g_alibi = 0.0f, g_hi = 0.0f, g_lo = 0.0f;
 
     f32x16 dq[D / 32];
 #pragma unroll
@@ -517,6 +539,30 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) dpacc[r] = mrow(kv0_cur + kvb * 32 + crow(r, half)) ? dpacc[r] : 0.0f;
             }
+            if constexpr (CAPTURED) {
+                const int kvs = kv0_cur + kvb * 32;
+                if constexpr (ScoreMod<SCORE>::kAlibi) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        g_alibi = __builtin_fmaf(dpacc[r], (float)(q_pos - (kvs + crow(r, half))), g_alibi);
+                }
+                if constexpr (ScoreMod<SCORE>::kRel) {
+                    if (q_wave_min - (kvs + 31) >= smod.rel_max) {          // every pair on the last entry
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) g_hi += dpacc[r];
+                    } else if (q_wave_min + 31 <= kvs) {                     // every pair on the first entry
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) g_lo += dpacc[r];
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int dqk = q_pos - (kvs + crow(r, half));
+                            atomicAdd(&s_tab[dqk < 0 ? 0 : (dqk > smod.rel_max ? smod.rel_max : dqk)], dpacc[r]);
+                        }
+                    }
+                }
+                return;
+            }
             // dQ^T += K^T dS^T
             u32x4 dsk[2];
 #pragma unroll
@@ -549,6 +595,29 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
         if (t < T) step(t, std::integral_constant<int, 0>{});
     }
 
+    if constexpr (CAPTURED) {
+        auto wave_sum = [](float v) {
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+            return v;
+        };
+        if constexpr (ScoreMod<SCORE>::kAlibi) {
+            const float g = wave_sum(g_alibi);
+            if (lane == 0) atomicAdd(&s_tab[kTabAlibi], g);
+        }
+        if constexpr (ScoreMod<SCORE>::kRel) {
+            const float hi = wave_sum(g_hi), lo = wave_sum(g_lo);
+            if (lane == 0) {
+                atomicAdd(&s_tab[smod.rel_max], hi);
+                atomicAdd(&s_tab[0], lo);
+            }
+        }
+        __syncthreads();
+        if constexpr (ScoreMod<SCORE>::kRel)
+            for (int i = tid; i < a.p.rel_len; i += NW * 64) a.cap_rel[cap_slot * a.p.rel_len + i] = s_tab[i];
+        if constexpr (ScoreMod<SCORE>::kAlibi)
+            if (tid == 0) a.cap_alibi[cap_slot] = s_tab[kTabAlibi];
+        return;
+    }
     const float qscale = a.scale * ScoreMod<SCORE>::grad_scale();
     if (!real_row) return;
 #pragma unroll
@@ -561,6 +630,8 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
             *(u32x2*)(dq_ptr + db * 32 + 8 * rg + 4 * half) = pk;
         }
 }
+
+constexpr uint32_t kBwdStageCaptured = 8u;   // internal: the captured-tensor sums instead of dQ
 
 template <uint32_t MASK, uint32_t SCORE>
 int launch_bwd_variant(const BwdArgs& a, int D, uint32_t stages, hipStream_t st) {
@@ -581,6 +652,16 @@ int launch_bwd_variant(const BwdArgs& a, int D, uint32_t stages, hipStream_t st)
         if (kv) hipLaunchKernelGGL((bwd_dkdv_kernel<64, MASK, SCORE>), dim3(grid_kv), dim3(256), 0, st, a);
         if (q && a.Bq == 128) hipLaunchKernelGGL((bwd_dq_kernel<64, 4, MASK, SCORE>), dim3(grid_q), dim3(256), 0, st, a);
         if (q && a.Bq == 64) hipLaunchKernelGGL((bwd_dq_kernel<64, 2, MASK, SCORE>), dim3(grid_q), dim3(128), 0, st, a);
+    }
+    if (stages & kBwdStageCaptured) {
+        if constexpr ((SCORE & (FLEXATTN_SCORE_ALIBI | FLEXATTN_SCORE_REL_BIAS)) != 0) {
+            if (D == 128 && a.Bq == 128) hipLaunchKernelGGL((bwd_dq_kernel<128, 4, MASK, SCORE, true>), dim3(grid_q), dim3(256), 0, st, a);
+            else if (D == 128) hipLaunchKernelGGL((bwd_dq_kernel<128, 2, MASK, SCORE, true>), dim3(grid_q), dim3(128), 0, st, a);
+            else if (a.Bq == 128) hipLaunchKernelGGL((bwd_dq_kernel<64, 4, MASK, SCORE, true>), dim3(grid_q), dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((bwd_dq_kernel<64, 2, MASK, SCORE, true>), dim3(grid_q), dim3(128), 0, st, a);
+        } else {
+            return FLEXATTN_ERR_UNSUPPORTED;     // this score_mod captures no tensor
+        }
     }
     return FLEXATTN_OK;
 }
