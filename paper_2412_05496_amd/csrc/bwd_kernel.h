@@ -147,6 +147,15 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
         }
     }
 
+    {   // the score GEMM's K operand carries the factor of the score (see ScoreMod, PRESCALED); it does
+        // not depend on the head
+        const ScoreMod<SCORE, true> smod0(a.p, hkv * a.G, a.scale);
+        if constexpr (ScoreMod<SCORE>::kBwdGainsFromPrescale) {
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) kf[ks] = scale_bf16x8(kf[ks], smod0.k_acc);
+        }
+    }
+
     f32x16 acc[NDB];                    // x = 0: dV^T, x = 1: dK^T (row = dim, column = key)
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -183,7 +192,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
         // waves 0, 2 fetch the rc row, waves 1, 3 the -delta row (the duplicates write the same values)
         const i32x4 row_rsrc =
             make_rsrc(((w & 1) ? a.delta : a.lse2) + ((int64_t)b * a.Hq + hq) * a.q_len, (uint32_t)a.q_len * 4u);
-        const ScoreMod<SCORE> smod(a.p, hq, a.scale);
+        const ScoreMod<SCORE, ScoreMod<SCORE>::kBwdGainsFromPrescale> smod(a.p, hq, a.scale);
 
         // The merged list (FULL blocks, then PARTIAL ones) is walked from its END: every workgroup of
         // a head then spends most of its time descending from the last row block, so the workgroups
@@ -446,7 +455,11 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
     const i32x4 k_rsrc = make_rsrc(a.K + b * a.k_sb + hkv * a.k_sh, (uint32_t)((a.kv_len - 1) * a.k_ss + D) * 2u);
     const i32x4 v_rsrc = make_rsrc(a.V + b * a.v_sb + hkv * a.v_sh, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
     const int k_row_bytes = (int)a.k_ss * 2, v_row_bytes = (int)a.v_ss * 2;
-    const ScoreMod<SCORE> smod(a.p, hq, a.scale);
+    const ScoreMod<SCORE, ScoreMod<SCORE>::kBwdGainsFromPrescale> smod(a.p, hq, a.scale);
+    if constexpr (ScoreMod<SCORE>::kBwdGainsFromPrescale) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) qf[ks] = scale_bf16x8(qf[ks], smod.k_acc);   // see ScoreMod, PRESCALED
+    }
     const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
     const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
 

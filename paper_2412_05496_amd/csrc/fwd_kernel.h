@@ -125,7 +125,9 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
         }
     };
 
-    const ScoreMod<SCORE> smod(a.p, hq, a.scale);
+    const ScoreMod<SCORE, true> smod(a.p, hq, a.scale);
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) qf[ks] = scale_bf16x8(qf[ks], smod.k_acc);   // see ScoreMod, PRESCALED
     const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
     const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
     const float inv_neg2c = smod.capl2 > 0.0f ? -0.5f / smod.capl2 : 0.0f;   // 1 / (-2 cap log2 e)
