@@ -145,3 +145,24 @@ def test_forward_is_deterministic_and_strided_inputs_work():
     fa.flexattn_forward(Qs, Ks, Vs, score_id, mask_id, params, bm, inp.scale, O3, L3)
     torch.cuda.synchronize()
     assert torch.equal(O3, O1) and torch.equal(L3, L1)
+
+
+def test_backward_strided_layout_and_stages_agree():
+    """[B, S, H, D] memory layout for every tensor of the backward, and the stages run one by one, give
+    bit for bit what the dense single call gives."""
+    import paper_2412_05496_amd as fa
+    wl = SMALL["cfg2_small"].scaled(S=1000, Hq=4, Hkv=2)          # a cut last block and GQA as well
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    O, LSE, bm, ids = run_forward(wl, inp, DEV)
+    dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids)
+    mask_id, score_id, params, Q, K, V = ids
+    bshd = lambda t: t.transpose(1, 2).contiguous().transpose(1, 2)
+    Qs, Ks, Vs, Os, dOs = (bshd(t) for t in (Q, K, V, O, inp.dO.to(DEV)))
+    dQs, dKs, dVs = (bshd(torch.full_like(t, float("nan"))) for t in (Q, K, V))
+    ws = torch.empty(fa.flexattn_backward_workspace_bytes(Q, K), dtype=torch.uint8, device=DEV)
+    for stage in (fa.BWD_DELTA, fa.BWD_DQ, fa.BWD_DKDV):
+        fa.flexattn_backward_stages(Qs, Ks, Vs, Os, dOs, LSE, score_id, mask_id, params, bm, inp.scale,
+                                    dQs if stage == fa.BWD_DQ else None, dKs if stage == fa.BWD_DKDV else None,
+                                    dVs if stage == fa.BWD_DKDV else None, ws, stage)
+    torch.cuda.synchronize()
+    assert torch.equal(dQs, dQ) and torch.equal(dKs, dK) and torch.equal(dVs, dV)
