@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const BwdArgs a) {
 // issued at the top of step v.  Two barriers per step: after the exchange writes, and at the end
 // (exchange buffer and ring slot free again, next tiles landed).
 template <int D, uint32_t MASK, uint32_t SCORE>
-__global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
+__global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv_kernel(const BwdArgs a) {
     constexpr int TQ = 64;                         // query rows per step
     constexpr int TILE = TQ * D;                   // elements per LDS tile
     constexpr int NKS = D / 16, NDB = D / 32;
@@ -395,7 +395,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkdv_kernel(const BwdArgs a) {
 // One partial result per workgroup; the blocks whose every pair falls on the table's last (or first)
 // entry are summed in registers, the others entry by entry with LDS atomics.
 template <int D, int NW, uint32_t MASK, uint32_t SCORE, bool CAPTURED = false>
-__global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(const BwdArgs a) {
+__global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_dq_kernel(const BwdArgs a) {
     constexpr int Bq = NW * 32;
     constexpr int TILE = 64 * D;
     __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];   // K(even), K(odd), V(even), V(odd)

@@ -55,7 +55,7 @@ constexpr int kTileKV = 64;   // keys per kernel tile
 // PAGED: the tiles of K and V are fetched from a paged pool through the converted block lists;
 // the mods keep seeing the logical key index.
 template <int D, int NW, uint32_t MASK, uint32_t SCORE, bool BOUNDED, bool PAGED = false>
-__global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(const FwdArgs a) {
+__global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void fwd_kernel(const FwdArgs a) {
     constexpr int Bq = NW * 32;
     constexpr int TILE = kTileKV * D;              // elements per LDS tile
 
