@@ -493,6 +493,10 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
         constexpr int BUF = decltype(buf_tag)::value;
         const int kv0_cur = kv0;
         const bool partial = part_next;
+        int tile_docs = 0;          // document ids of this tile's keys: one coalesced read, used after the MFMAs
+        if constexpr (MaskRow<MASK>::kUsesDoc) {
+            if (partial) tile_docs = MaskRow<MASK>::tile_docs(a.p, b, kv0_cur, a.kv_len - 1, lane);
+        }
         // K(t+1), V(t+1) go to buffer BUF ^ 1, last read in step t-1.  Their loads are issued piece by
         // piece between the first MFMAs below: a wave waits on every load instruction until the
         // memory pipe has taken it.
@@ -550,7 +554,13 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
             if (partial) {
                 asm volatile("" ::: "memory");   // keep this a branch
 #pragma unroll
-                for (int r = 0; r < 16; ++r) dpacc[r] = mrow(kv0_cur + kvb * 32 + crow(r, half)) ? dpacc[r] : 0.0f;
+                for (int r = 0; r < 16; ++r) {
+                    const int off = kvb * 32 + crow(r, half);
+                    bool keep;
+                    if constexpr (MaskRow<MASK>::kUsesDoc) keep = mrow.eval(kv0_cur + off, MaskRow<MASK>::doc_at(tile_docs, off));
+                    else keep = mrow(kv0_cur + off);
+                    dpacc[r] = keep ? dpacc[r] : 0.0f;
+                }
             }
             if constexpr (CAPTURED) {
                 const int kvs = kv0_cur + kvb * 32;

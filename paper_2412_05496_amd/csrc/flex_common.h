@@ -141,7 +141,9 @@ struct MaskTermRow {
     // NEIGHBORHOOD: the window of the query pixel, [x0, x0 + span] x [y0, y0 + span]
     std::conditional_t<(TERM & FLEXATTN_M_NEIGHBORHOOD) != 0, CanvasOrder, NoCanvas> canvas;
     int x0, y0, span;
-    __device__ __forceinline__ MaskTermRow(const flexattn_mod_params& p, int b, int /*h*/, int q_idx) : canvas(p) {
+    // doc_q_known >= 0: the caller already holds doc_ids[b, q_idx] (no table read here)
+    __device__ __forceinline__ MaskTermRow(const flexattn_mod_params& p, int b, int /*h*/, int q_idx, int doc_q_known = -1)
+        : canvas(p) {
         q = q_idx;
         window = p.window;
         prefix_len = p.prefix_len;
@@ -159,15 +161,21 @@ struct MaskTermRow {
         }
         if constexpr (TERM & FLEXATTN_M_DOCUMENT) {
             doc_row = p.doc_ids + (int64_t)b * p.doc_stride_b;
-            doc_q = doc_row[q_idx];
+            doc_q = doc_q_known >= 0 ? doc_q_known : doc_row[q_idx];
         }
         if constexpr (TERM & FLEXATTN_M_CTX_LEN) ctx = p.ctx_lens[b];
     }
     __device__ __forceinline__ bool operator()(int kv) const {
+        int doc_kv = 0;
+        if constexpr (TERM & FLEXATTN_M_DOCUMENT) doc_kv = doc_row[kv];
+        return eval(kv, doc_kv);
+    }
+    // the same with doc_ids[b, kv] supplied by the caller
+    __device__ __forceinline__ bool eval(int kv, int doc_kv) const {
         bool r = true;
         if constexpr (TERM & FLEXATTN_M_CAUSAL) r = r && (q >= kv);
         if constexpr (TERM & FLEXATTN_M_SLIDING_WINDOW) r = r && (q - kv <= window);
-        if constexpr (TERM & FLEXATTN_M_DOCUMENT) r = r && (doc_row[kv] == doc_q);
+        if constexpr (TERM & FLEXATTN_M_DOCUMENT) r = r && (doc_kv == doc_q);
         if constexpr (TERM & FLEXATTN_M_PREFIX) r = r && (kv < prefix_len);
         if constexpr (TERM & FLEXATTN_M_CTX_LEN) r = r && (kv < ctx);
         if constexpr (TERM & FLEXATTN_M_NEIGHBORHOOD) {
@@ -191,11 +199,26 @@ struct MaskRow {
     MaskTermRow<T0> t0;
     MaskTermRow<T1> t1;
     int kv_last;
+    // Masks that read the document table can take the ids from the caller instead, who fetches
+    // them for a whole tile with one coalesced load (lane j: entry first + j) and hands them from
+    // lane to lane (tile_docs / doc_at), rather than with one table read per score element.
+    static constexpr bool kUsesDoc = (((MASK | (MASK >> 8)) & 0xffu) & FLEXATTN_M_DOCUMENT) != 0;
+    __device__ __forceinline__ static int tile_docs(const flexattn_mod_params& p, int b, int first, int last, int lane) {
+        return (p.doc_ids + (int64_t)b * p.doc_stride_b)[min(first + lane, last)];
+    }
+    __device__ __forceinline__ static int doc_at(int docs, int offset_in_tile) { return __shfl(docs, offset_in_tile, 64); }
     // kv_len: keys at or past it do not exist (last block of a length that is no multiple of the
     // block size): they are masked, and the primitives are evaluated at the last real key instead
     // so that no table is read out of range.  q_idx must be a real row.
-    __device__ __forceinline__ MaskRow(const flexattn_mod_params& p, int b, int h, int q_idx, int kv_len)
-        : t0(p, b, h, q_idx), t1(p, b, h, q_idx), kv_last(kv_len - 1) {}
+    __device__ __forceinline__ MaskRow(const flexattn_mod_params& p, int b, int h, int q_idx, int kv_len,
+                                       int doc_q_known = -1)
+        : t0(p, b, h, q_idx, doc_q_known), t1(p, b, h, q_idx, doc_q_known), kv_last(kv_len - 1) {}
+    // with the document id of key kv supplied (any value for keys past the end)
+    __device__ __forceinline__ bool eval(int kv, int doc_kv) const {
+        bool r = t0.eval(kv, doc_kv);
+        if constexpr (T1 != 0) r = r || t1.eval(kv, doc_kv);
+        return r && kv <= kv_last;
+    }
     __device__ __forceinline__ bool operator()(int kv) const {
         const int kc = min(kv, kv_last);
         bool r = t0(kc);

@@ -184,6 +184,11 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
     // score_mod, mask_mod (partial blocks only) and softmax of one 32-key block whose first key is
     // kvs: s -> P^T as two bf16 fragments.  The mask is a separate, rarely taken pass (kept a real
     // branch) so that the common path is one straight run of VALU work next to the MFMAs around it.
+    int tile_docs = 0, tile_first = 0;   // document ids of the current tile's keys (partial tiles of document masks)
+    auto keep = [&](int kv) __attribute__((always_inline)) {
+        if constexpr (MaskRow<MASK>::kUsesDoc) return mrow.eval(kv, MaskRow<MASK>::doc_at(tile_docs, kv - tile_first));
+        else return mrow(kv);
+    };
     auto softmax = [&](f32x16& s, int kvs, bool partial, bf16x8 (&pf)[2]) {
         const int dq_base = q_pos - kvs;
         if constexpr (BOUNDED) {
@@ -197,7 +202,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
             if (partial) {
                 asm volatile("" ::: "memory");   // keep this a branch, not 16 selects on every tile
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = mrow(kvs + crow(r, half)) ? s[r] : 0.0f;
+                for (int r = 0; r < 16; ++r) s[r] = keep(kvs + crow(r, half)) ? s[r] : 0.0f;
             }
         } else {
 #pragma unroll
@@ -205,7 +210,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
             if (partial) {
                 asm volatile("" ::: "memory");
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = mrow(kvs + crow(r, half)) ? s[r] : -INFINITY;
+                for (int r = 0; r < 16; ++r) s[r] = keep(kvs + crow(r, half)) ? s[r] : -INFINITY;
             }
             float mx = s[0];
 #pragma unroll
@@ -284,6 +289,12 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
         tile_src(v_head, v_rsrc, v_row_bytes, kv_t1, pg_t1, pr_t1, v_src, v_soff);
         const int kv0 = kv_t;
         const bool partial = part_t;
+        if constexpr (MaskRow<MASK>::kUsesDoc) {
+            if (partial) {      // one coalesced read, behind the MFMAs that follow
+                tile_first = kv0;
+                tile_docs = MaskRow<MASK>::tile_docs(a.p, b, kv0, a.kv_len - 1, lane);
+            }
+        }
         bf16x8 pf[2];
         if constexpr (HAS_NEXT) {
             using L = WaveTileLoader<D, NW>;
