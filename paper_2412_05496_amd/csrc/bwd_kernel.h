@@ -295,14 +295,20 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
 #pragma unroll
                 for (int c4 = 0; c4 < 4; ++c4) {
                     float sv[4], rcv[4], gr[4], pe[4], ds[4];
-                    int dqk[4];
+                    // alibi / rel-bias need q - kv = dq0 + 8 (r >> 2) + (r & 3); the soft-cap and the plain score do not
+                    using RelPos = typename decltype(smod)::RelPos;
+                    constexpr bool kNeedsPos = ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel;
+                    const int dq0 = kNeedsPos ? q_off + q_first + 4 * half - kv_lane : 0;
+                    const float abase = smod.alibi_base(dq0);
+                    auto rel = [&](int r) __attribute__((always_inline)) {
+                        return kNeedsPos ? RelPos(dq0, abase, 8 * (r >> 2) + (r & 3)) : RelPos(0);
+                    };
+                    const RelPos dqk[4] = {rel(4 * c4), rel(4 * c4 + 1), rel(4 * c4 + 2), rel(4 * c4 + 3)};
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int r = 4 * c4 + i;
                         sv[i] = sacc[r];
                         rcv[i] = rcv4[r >> 2][r & 3];
-                        // alibi / rel-bias need q - kv; the soft-cap and the plain score do not
-                        dqk[i] = (ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel) ? q_off + q_first + crow(r, half) - kv_lane : 0;
                     }
                     smod.p_with_grad4(sv, dqk, rcv, gr, pe);
 #pragma unroll
@@ -544,11 +550,14 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
                     __builtin_amdgcn_sched_barrier(0);
                 });
             }
+            // q_idx - kv_idx of element r is dq0 - 8 (r >> 2) - (r & 3)
+            const int dq0 = q_pos - (kv0_cur + kvb * 32 + 4 * half);
+            const float abase = smod.alibi_base(dq0);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int kv = kv0_cur + kvb * 32 + crow(r, half);
                 float gr;
-                const float pe = smod.p_with_grad(sacc[r], q_pos - kv, rc, gr);
+                const float pe = smod.p_with_grad(sacc[r], typename decltype(smod)::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3))),
+                                                  rc, gr);
                 dpacc[r] = pe * gr * dpacc[r];
             }
             if (partial) {

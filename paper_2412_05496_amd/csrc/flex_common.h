@@ -266,23 +266,35 @@ struct ScoreMod {
         capl2 = kCap ? p.softcap * kLog2e : 0.0f;
     }
 
+    // q_idx - kv_idx of one score element.  The kernels know it as dq0 + c with dq0 shared by the 16
+    // elements a lane holds of a 32 x 32 block and c a compile-time constant, so the ALiBi term
+    // bias * (dq0 + c) costs one addition of abase = alibi_base(dq0), computed once per block, and
+    // one fma with a literal instead of a subtraction, a conversion and an fma per element.
+    struct RelPos {
+        int dq;
+        float abase, c;
+        __device__ __forceinline__ RelPos(int dq_) : dq(dq_), abase(0.0f), c((float)dq_) {}
+        __device__ __forceinline__ RelPos(int dq0, float abase_, int c_) : dq(dq0 + c_), abase(abase_), c((float)c_) {}
+    };
+    __device__ __forceinline__ float alibi_base(int dq0) const { return kAlibi ? k_bias * (float)dq0 : 0.0f; }
+
     // Scaled score plus the additive biases, times the factor the following exp2 needs.
-    __device__ __forceinline__ float pre(float acc, int dq) const {
+    __device__ __forceinline__ float pre(float acc, RelPos rp) const {
         float y = PRESCALED ? acc : acc * k_acc;
-        if constexpr (kAlibi) y = __builtin_fmaf(k_bias, (float)dq, y);
+        if constexpr (kAlibi) y = __builtin_fmaf(k_bias, rp.c, y + rp.abase);
         if constexpr (kRel) {
-            int r = dq < 0 ? 0 : (dq > rel_max ? rel_max : dq);
+            int r = rp.dq < 0 ? 0 : (rp.dq > rel_max ? rel_max : rp.dq);
             y = __builtin_fmaf(tab[r], k_tab, y);
         }
         return y;
     }
 
     // Soft-cap only: r = 1 / (1 + exp(2 s / cap)), so that cap * tanh(s / cap) = cap * (1 - 2 r).
-    __device__ __forceinline__ float cap_r(float acc, int dq) const {
+    __device__ __forceinline__ float cap_r(float acc, RelPos dq) const {
         return fast_rcp(1.0f + fast_exp2(pre(acc, dq)));
     }
 
-    __device__ __forceinline__ float apply(float acc, int dq) const {
+    __device__ __forceinline__ float apply(float acc, RelPos dq) const {
         if constexpr (kCap) {
             return __builtin_fmaf(-2.0f * capl2, cap_r(acc, dq), capl2);
         } else {
@@ -306,7 +318,7 @@ struct ScoreMod {
     // The same for four independent elements, written stage by stage (pin4 keeps the stages apart):
     // a wave that is alone on its SIMD loses several cycles on every vector instruction that
     // consumes the result of the one before it.
-    __device__ __forceinline__ void p_with_grad4(const float (&acc)[4], const int (&dq)[4], const float (&rc)[4],
+    __device__ __forceinline__ void p_with_grad4(const float (&acc)[4], const RelPos (&dq)[4], const float (&rc)[4],
                                                  float (&g)[4], float (&p)[4]) const {
         float x[4];
 #pragma unroll
@@ -340,7 +352,7 @@ struct ScoreMod {
         for (int i = 0; i < 4; ++i) p[i] = fast_exp2(x[i]);
         pin4(p);
     }
-    __device__ __forceinline__ float p_with_grad(float acc, int dq, float rc, float& g) const {
+    __device__ __forceinline__ float p_with_grad(float acc, RelPos dq, float rc, float& g) const {
         if constexpr (kCap) {
             const float r = cap_r(acc, dq);
             g = __builtin_fmaf(-r, r, r);

@@ -190,13 +190,18 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
         else return mrow(kv);
     };
     auto softmax = [&](f32x16& s, int kvs, bool partial, bf16x8 (&pf)[2]) {
-        const int dq_base = q_pos - kvs;
+        // q_idx - kv_idx of element r is dq0 - 8 (r >> 2) - (r & 3)
+        const int dq0 = q_pos - kvs - 4 * half;
+        const float abase = smod.alibi_base(dq0);
+        auto rel = [&](int r) __attribute__((always_inline)) {
+            return typename ScoreMod<SCORE, true>::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3)));
+        };
         if constexpr (BOUNDED) {
             // p = 2^(x - cap log2 e) = 2^(-2 cap log2 e * r), r = 1 / (1 + e): no maximum to track
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 // -2 cap log2e / (1 + e) as ONE reciprocal: rcp((1 + e) / (-2 cap log2e))
-                const float e = fast_exp2(smod.pre(s[r], dq_base - crow(r, half)));
+                const float e = fast_exp2(smod.pre(s[r], rel(r)));
                 s[r] = fast_exp2(fast_rcp(__builtin_fmaf(e, inv_neg2c, inv_neg2c)));
             }
             if (partial) {
@@ -206,7 +211,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
             }
         } else {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = smod.apply(s[r], dq_base - crow(r, half));
+            for (int r = 0; r < 16; ++r) s[r] = smod.apply(s[r], rel(r));
             if (partial) {
                 asm volatile("" ::: "memory");
 #pragma unroll
