@@ -147,15 +147,6 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
         }
     }
 
-    {   // the score GEMM's K operand carries the factor of the score (see ScoreMod, PRESCALED); it does
-        // not depend on the head
-        const ScoreMod<SCORE, true> smod0(a.p, hkv * a.G, a.scale);
-        if constexpr (ScoreMod<SCORE>::kBwdGainsFromPrescale) {
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) kf[ks] = scale_bf16x8(kf[ks], smod0.k_acc);
-        }
-    }
-
     f32x16 acc[NDB];                    // x = 0: dV^T, x = 1: dK^T (row = dim, column = key)
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -192,7 +183,7 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
         // waves 0, 2 fetch the rc row, waves 1, 3 the -delta row (the duplicates write the same values)
         const i32x4 row_rsrc =
             make_rsrc(((w & 1) ? a.delta : a.lse2) + ((int64_t)b * a.Hq + hq) * a.q_len, (uint32_t)a.q_len * 4u);
-        const ScoreMod<SCORE, ScoreMod<SCORE>::kBwdGainsFromPrescale> smod(a.p, hq, a.scale);
+        const ScoreMod<SCORE> smod(a.p, hq, a.scale);
 
         // The merged list (FULL blocks, then PARTIAL ones) is walked from its END: every workgroup of
         // a head then spends most of its time descending from the last row block, so the workgroups
@@ -461,11 +452,7 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
     const i32x4 k_rsrc = make_rsrc(a.K + b * a.k_sb + hkv * a.k_sh, (uint32_t)((a.kv_len - 1) * a.k_ss + D) * 2u);
     const i32x4 v_rsrc = make_rsrc(a.V + b * a.v_sb + hkv * a.v_sh, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
     const int k_row_bytes = (int)a.k_ss * 2, v_row_bytes = (int)a.v_ss * 2;
-    const ScoreMod<SCORE, ScoreMod<SCORE>::kBwdGainsFromPrescale> smod(a.p, hq, a.scale);
-    if constexpr (ScoreMod<SCORE>::kBwdGainsFromPrescale) {
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) qf[ks] = scale_bf16x8(qf[ks], smod.k_acc);   // see ScoreMod, PRESCALED
-    }
+    const ScoreMod<SCORE> smod(a.p, hq, a.scale);
     const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
     const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
 

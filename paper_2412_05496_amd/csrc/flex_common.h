@@ -64,14 +64,6 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 // Exchange a value with the lane 32 away (the other half of the wave).
 __device__ __forceinline__ float swap_halves(float v) { return __shfl_xor(v, 32, 64); }
 
-// Fragment times a scalar, rounded back to bf16.
-__device__ __forceinline__ bf16x8 scale_bf16x8(bf16x8 v, float k) {
-    bf16x8 r;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (bf16)((float)v[i] * k);
-    return r;
-}
-
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     bf16x2 v;
     v[0] = (bf16)lo;
@@ -238,17 +230,11 @@ __device__ __forceinline__ void pin4(float (&v)[4]) {
     asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
 }
 
-// PRESCALED: the caller has multiplied one operand of the score GEMM by k_acc (the fragments that
-// stay in registers for the whole kernel, re-rounded to bf16), so the accumulator already carries
-// the factor and every element saves one multiplication.
-template <uint32_t SCORE, bool PRESCALED = false>
+template <uint32_t SCORE>
 struct ScoreMod {
     static constexpr bool kAlibi = SCORE & FLEXATTN_SCORE_ALIBI;
     static constexpr bool kRel = SCORE & FLEXATTN_SCORE_REL_BIAS;
     static constexpr bool kCap = SCORE & FLEXATTN_SCORE_SOFTCAP;
-    // In the backward a plain score folds its factor into the fma that adds the row constant, so
-    // only the other score_mods gain from a pre-scaled operand there.
-    static constexpr bool kBwdGainsFromPrescale = kAlibi || kRel || kCap;
     float k_acc;      // multiplies the raw dot product
     float k_bias;     // alibi_bias[h], pre-multiplied like k_acc
     float k_tab;      // factor applied to table entries
@@ -280,7 +266,7 @@ struct ScoreMod {
 
     // Scaled score plus the additive biases, times the factor the following exp2 needs.
     __device__ __forceinline__ float pre(float acc, RelPos rp) const {
-        float y = PRESCALED ? acc : acc * k_acc;
+        float y = acc * k_acc;
         if constexpr (kAlibi) y = __builtin_fmaf(k_bias, rp.c, y + rp.abase);
         if constexpr (kRel) {
             int r = rp.dq < 0 ? 0 : (rp.dq > rel_max ? rel_max : rp.dq);

@@ -125,9 +125,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
         }
     };
 
-    const ScoreMod<SCORE, true> smod(a.p, hq, a.scale);
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) qf[ks] = scale_bf16x8(qf[ks], smod.k_acc);   // see ScoreMod, PRESCALED
+    const ScoreMod<SCORE> smod(a.p, hq, a.scale);
     const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
     const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
     const float inv_neg2c = smod.capl2 > 0.0f ? -0.5f / smod.capl2 : 0.0f;   // 1 / (-2 cap log2 e)
@@ -194,7 +192,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
         const int dq0 = q_pos - kvs - 4 * half;
         const float abase = smod.alibi_base(dq0);
         auto rel = [&](int r) __attribute__((always_inline)) {
-            return typename ScoreMod<SCORE, true>::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3)));
+            return typename ScoreMod<SCORE>::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3)));
         };
         if constexpr (BOUNDED) {
             // p = 2^(x - cap log2 e) = 2^(-2 cap log2 e * r), r = 1 / (1 + e): no maximum to track

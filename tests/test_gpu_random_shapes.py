@@ -29,17 +29,20 @@ def draw(seed):
               backward=True, softcap=rng.choice([5.0, 30.0, 60.0]), window=rng.randint(0, 300),
               prefix_len=rng.randint(0, 200), rel_len=rng.choice([1, 17, 64]),
               doc_len_min=rng.randint(1, 40), doc_len_max=rng.randint(40, 400))
-    return wlm.CFG1.scaled(**kw), Lq
+    scale = rng.choice([None, None, 0.3, 0.02])       # None: 1 / sqrt(D)
+    return wlm.CFG1.scaled(**kw), Lq, scale
 
 
 @pytest.mark.parametrize("seed", range(40))
 def test_random_shape(seed):
     import paper_2412_05496_amd as fa
-    wl, Lq = draw(seed)
+    wl, Lq, scale = draw(seed)
     dev = torch.device("cuda:0")
     print(f"case {seed}: {wl.mask}/{wl.score} B={wl.B} Hq={wl.Hq} Hkv={wl.Hkv} Lq={Lq} S={wl.S} D={wl.D} "
-          f"block={wl.Bq}x{wl.Bk}", flush=True)
+          f"block={wl.Bq}x{wl.Bk} scale={scale}", flush=True)
     inp = wlm.make_train_inputs(wl, with_dO=True)
+    if scale is not None:
+        inp.scale = scale
     Q, dO = inp.Q[:, :, :Lq].contiguous(), inp.dO[:, :, :Lq].contiguous()
     score_mod, mask_mod = hp.oracle_mods(wl, inp)
     O_ref, LSE_ref = fo.flex_attention(Q, inp.K, inp.V, score_mod, mask_mod, inp.scale)
