@@ -352,12 +352,12 @@ struct ScoreMod {
 
 // Waves per SIMD the MFMA kernels are compiled for.  At D = 64 the lean variants fit 168 registers,
 // so three workgroups share a CU (more latency hiding, more chances for one wave's MFMAs to run
-// beside another's VALU work); the variants that carry a document table, a relative-bias table or
-// the canvas decode would spill there and stay at two, as does everything at D = 128.
+// beside another's VALU work); the variants that carry a relative-bias table or the canvas decode
+// would spill there and stay at two, as does everything at D = 128.
 template <int D, uint32_t MASK, uint32_t SCORE>
 constexpr int waves_per_simd() {
     constexpr uint32_t prims = (MASK | (MASK >> 8)) & 0xffu;
-    constexpr bool lean = !(prims & (FLEXATTN_M_DOCUMENT | FLEXATTN_M_NEIGHBORHOOD)) && !(SCORE & FLEXATTN_SCORE_REL_BIAS);
+    constexpr bool lean = !(prims & FLEXATTN_M_NEIGHBORHOOD) && !(SCORE & FLEXATTN_SCORE_REL_BIAS);
     return (D == 64 && lean) ? 3 : 2;
 }
 
