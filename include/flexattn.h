@@ -25,7 +25,8 @@
  *     Head dimension D is 64 or 128 and has unit stride; other strides are in ELEMENTS.
  *   - Grouped-query attention: query head hq reads KV head hq / (Hq / Hkv); mods see hq.
  *   - A query row whose keys are all masked yields O = 0, LSE = -inf and zero gradients.
- *   - Results are deterministic run to run (no floating-point atomics).
+ *   - Results are deterministic run to run (no floating-point atomics), with the one exception
+ *     stated at flexattn_backward_captured.
  */
 #ifndef FLEXATTN_H
 #define FLEXATTN_H
@@ -101,7 +102,8 @@ typedef struct flexattn_mod_params {
     int32_t        prefix_len;    /* PREFIX                                                    */
     float          softcap;       /* SOFTCAP, > 0                                              */
     int32_t        rel_len;       /* REL_BIAS: row length of rel_bias (<= 1024)                */
-    const int32_t* doc_ids;       /* DOCUMENT: [B, seq] token -> document index                */
+    const int32_t* doc_ids;       /* DOCUMENT: [B, seq] token -> document index; read at the
+                                     positions the mods see (q_idx + q_offsets[b], kv_idx)       */
     int64_t        doc_stride_b;  /*           elements between batches (0 = shared row)       */
     const float*   alibi_bias;    /* ALIBI: [Hq] fp32                                          */
     const float*   rel_bias;      /* REL_BIAS: [Hq, rel_len] fp32, row-major                   */
