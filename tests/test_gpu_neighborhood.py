@@ -85,3 +85,35 @@ def test_bad_canvas_parameters_are_refused():
     for kw in bad:
         with pytest.raises(fa.FlexAttnError):
             fa.flexattn_blockmask_build(fa.MASK_NEIGHBORHOOD, fa.ModParams(**kw), bm)
+
+
+@pytest.mark.parametrize("layout,tile", [("row_major", 0), ("tiled", 8), ("tiled", 32), ("morton", 0)])
+def test_blockmask_on_a_large_canvas_sampled_blocks(layout, tile):
+    """128 x 128 pixels (16384 tokens): the kind of 300 sampled blocks, and the unmasked-pair count of the
+    whole mask, against the oracle's mask evaluated on those blocks only."""
+    import paper_2412_05496_amd as fa
+    W = H = 128
+    K, Bq, Bk = 13, 128, 64
+    S = W * H
+    dev = torch.device("cuda:0")
+    bm = fa.alloc_blockmask(1, 1, S, S, Bq, Bk, device=dev)
+    fa.flexattn_blockmask_build(fa.MASK_NEIGHBORHOOD, na_params(fa, W, H, K, layout, tile), bm)
+    torch.cuda.synchronize()
+    stats = bm.stats.cpu().tolist()
+    assert stats[3] == S * K * K and stats[2] == (S // Bq) * (S // Bk)
+    num, idx = bm.kv_num_blocks.cpu()[0, 0], bm.kv_indices.cpu()[0, 0]
+    fnum, fidx = bm.full_kv_num_blocks.cpu()[0, 0], bm.full_kv_indices.cpu()[0, 0]
+    mask = fo.neighborhood_mask(W, H, K, layout, tile)
+    g = torch.Generator().manual_seed(17)
+    rows = torch.randint(0, S // Bq, (300,), generator=g).tolist()
+    cols = torch.randint(0, S // Bk, (300,), generator=g).tolist()
+    # bias the sample towards blocks that are not empty: half of them are taken from the lists
+    for n, i in enumerate(rows[:150]):
+        if int(num[i]) > 0:
+            cols[n] = int(idx[i, n % int(num[i])])
+    for i, j in zip(rows, cols):
+        keep = mask(0, 0, torch.arange(i * Bq, (i + 1) * Bq).view(-1, 1), torch.arange(j * Bk, (j + 1) * Bk).view(1, -1))
+        cnt = int(keep.sum())
+        want = 0 if cnt == 0 else (2 if cnt == Bq * Bk else 1)
+        got = 1 if j in idx[i, :int(num[i])].tolist() else (2 if j in fidx[i, :int(fnum[i])].tolist() else 0)
+        assert got == want, (i, j, got, want)
