@@ -27,7 +27,20 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void classify_blocks_kernel(
         const int n = Bq * Bk;
         const int q_off = q_offset_of(p, b);
         int cnt = 0;
-        for (int e = lane; e < n; e += 64) {
+        // Blocks that lie wholly inside the score matrix and that the index comparisons of the mask
+        // settle as a whole are not enumerated; everything else is evaluated scalar by scalar.
+        bool settled = false;
+        if ((i + 1) * Bq <= q_len && (j + 1) * Bk <= kv_len) {
+            const MaskRow<MASK> corner(p, b, h, q_off + i * Bq, kv_len);
+            const int q_lo = q_off + i * Bq, q_hi = q_lo + Bq - 1, kv_lo = j * Bk, kv_hi = kv_lo + Bk - 1;
+            if (corner.block_empty(q_lo, q_hi, kv_lo, kv_hi)) {
+                settled = true;
+            } else if (corner.block_full(q_lo, q_hi, kv_lo, kv_hi)) {
+                settled = true;
+                cnt = lane == 0 ? n : 0;
+            }
+        }
+        for (int e = lane; e < (settled ? 0 : n); e += 64) {
             // rows and keys past the end of the score matrix count as masked
             const int q = i * Bq + e / Bk, kv = j * Bk + e % Bk;
             MaskRow<MASK> row(p, b, h, q_off + min(q, q_len - 1), kv_len);

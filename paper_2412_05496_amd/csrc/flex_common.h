@@ -162,6 +162,26 @@ struct MaskTermRow {
         if constexpr (TERM & FLEXATTN_M_DOCUMENT) doc_kv = doc_row[kv];
         return eval(kv, doc_kv);
     }
+    // Rectangle tests on q_lo <= q <= q_hi, kv_lo <= kv <= kv_hi, decided from the primitives that are
+    // plain index comparisons: block_empty is true only if NO pair can pass this term, block_full only
+    // if EVERY pair does (a term with a table lookup or the canvas decode is never declared full).
+    __device__ __forceinline__ bool block_empty(int q_lo, int q_hi, int kv_lo, int kv_hi) const {
+        bool e = false;
+        if constexpr (TERM & FLEXATTN_M_CAUSAL) e = e || (q_hi < kv_lo);
+        if constexpr (TERM & FLEXATTN_M_SLIDING_WINDOW) e = e || (q_lo - kv_hi > window);
+        if constexpr (TERM & FLEXATTN_M_PREFIX) e = e || (kv_lo >= prefix_len);
+        if constexpr (TERM & FLEXATTN_M_CTX_LEN) e = e || (kv_lo >= ctx);
+        return e;
+    }
+    __device__ __forceinline__ bool block_full(int q_lo, int q_hi, int kv_lo, int kv_hi) const {
+        if constexpr ((TERM & (FLEXATTN_M_DOCUMENT | FLEXATTN_M_NEIGHBORHOOD)) != 0) return false;
+        bool f = true;
+        if constexpr (TERM & FLEXATTN_M_CAUSAL) f = f && (q_lo >= kv_hi);
+        if constexpr (TERM & FLEXATTN_M_SLIDING_WINDOW) f = f && (q_hi - kv_lo <= window);
+        if constexpr (TERM & FLEXATTN_M_PREFIX) f = f && (kv_hi < prefix_len);
+        if constexpr (TERM & FLEXATTN_M_CTX_LEN) f = f && (kv_hi < ctx);
+        return f;
+    }
     // the same with doc_ids[b, kv] supplied by the caller
     __device__ __forceinline__ bool eval(int kv, int doc_kv) const {
         bool r = true;
@@ -205,6 +225,18 @@ struct MaskRow {
     __device__ __forceinline__ MaskRow(const flexattn_mod_params& p, int b, int h, int q_idx, int kv_len,
                                        int doc_q_known = -1)
         : t0(p, b, h, q_idx, doc_q_known), t1(p, b, h, q_idx, doc_q_known), kv_last(kv_len - 1) {}
+    // Whole-rectangle shortcuts (exact implications of the index comparisons, never a guess): the
+    // mask hides every pair / no pair of the rectangle.  The rectangle must lie inside the score matrix.
+    __device__ __forceinline__ bool block_empty(int q_lo, int q_hi, int kv_lo, int kv_hi) const {
+        bool e = T0 != 0 && t0.block_empty(q_lo, q_hi, kv_lo, kv_hi);
+        if constexpr (T1 != 0) e = e && t1.block_empty(q_lo, q_hi, kv_lo, kv_hi);
+        return e;
+    }
+    __device__ __forceinline__ bool block_full(int q_lo, int q_hi, int kv_lo, int kv_hi) const {
+        bool f = T0 == 0 || t0.block_full(q_lo, q_hi, kv_lo, kv_hi);
+        if constexpr (T1 != 0) f = f || t1.block_full(q_lo, q_hi, kv_lo, kv_hi);
+        return f;
+    }
     // with the document id of key kv supplied (any value for keys past the end)
     __device__ __forceinline__ bool eval(int kv, int doc_kv) const {
         bool r = t0.eval(kv, doc_kv);
