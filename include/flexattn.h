@@ -173,7 +173,9 @@ int flexattn_is_supported(uint32_t mask_id, uint32_t score_id, int32_t D);
 
 /* ---- BlockMask construction (section 4.2; create_block_mask, section 1.1) ----------
  * Evaluates mask_mod on every (q_idx, kv_idx) of every block -- brute force, so the result
- * is exact for any mask -- and fills the eight arrays of `bm` (both orientations).
+ * is exact for any mask; a block that the mask's index comparisons alone settle (every pair
+ * hidden, or none) is classified without the enumeration -- and fills the eight arrays of
+ * `bm` (both orientations).
  * Any q_len, kv_len >= 1.
  *   stats  nullable device int64[4]: {#partial blocks, #full blocks, #blocks, #unmasked
  *          scalars}, summed over Bm * Hm.
