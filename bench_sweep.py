@@ -48,31 +48,6 @@ def library_mods(fa, wl, inp, dev):
     return mask_id, score_id, params, (wl.B if wl.mask == "doc_causal" else 1)
 
 
-def all_partial(fa, bm):
-    """The same BlockMask with every FULL block listed as PARTIAL (mask_mod evaluated everywhere)."""
-    import torch
-    out = fa.alloc_blockmask(bm.Bm, bm.Hm, bm.q_len, bm.kv_len, bm.Bq, bm.Bk, device=bm.kv_num_blocks.device)
-    for num, idx, fnum, fidx, onum, oidx, ofnum, ofidx in (
-            (bm.kv_num_blocks, bm.kv_indices, bm.full_kv_num_blocks, bm.full_kv_indices,
-             out.kv_num_blocks, out.kv_indices, out.full_kv_num_blocks, out.full_kv_indices),
-            (bm.q_num_blocks, bm.q_indices, bm.full_q_num_blocks, bm.full_q_indices,
-             out.q_num_blocks, out.q_indices, out.full_q_num_blocks, out.full_q_indices)):
-        n = idx.shape[-1]
-        pos = torch.arange(n, device=idx.device)
-        big = torch.iinfo(torch.int32).max
-        a = torch.where(pos < num.unsqueeze(-1), idx, big)
-        b = torch.where(pos < fnum.unsqueeze(-1), fidx, big)
-        merged = torch.sort(torch.cat([a, b], dim=-1), dim=-1).values[..., :n]
-        total = num + fnum
-        oidx.copy_(torch.where(pos < total.unsqueeze(-1), merged, 0).to(torch.int32))
-        onum.copy_(total)
-        ofnum.zero_()
-        ofidx.zero_()
-    if bm.stats is not None and out.stats is not None:
-        out.stats.copy_(bm.stats)
-    return out
-
-
 def train_point(fa, wlm, wl, iters, tag, dev, force_partial=False):
     import torch
     inp = wlm.make_train_inputs(wl, with_dO=True)
@@ -83,7 +58,7 @@ def train_point(fa, wlm, wl, iters, tag, dev, force_partial=False):
     stats = bm.stats.cpu().tolist()
     pairs = stats[3] * (wl.B // Bm) * wl.Hq
     if force_partial:
-        bm = all_partial(fa, bm)
+        bm = wlm.blockmask_all_partial(fa.alloc_blockmask, bm)
     Q, K, V, dO = (t.to(dev) for t in (inp.Q, inp.K, inp.V, inp.dO))
     O = torch.empty_like(Q)
     LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=dev)

@@ -210,3 +210,28 @@ def make_prefill_inputs(wl: Workload, kv_lens: list[int], q_len: int, slack_page
     Q = randn_bf16(gen, wl.B, wl.Hq, q_len, wl.D)
     return PrefillInputs(wl, Q, d.K_pool, d.V_pool, d.page_table, d.ctx_lens,
                          (d.ctx_lens - q_len).to(torch.int32).contiguous(), d.scale)
+
+
+def blockmask_all_partial(alloc_blockmask, bm):
+    """The same BlockMask with every FULL block listed as PARTIAL, i.e. the full-block optimisation
+    switched off (index-list surgery only; `alloc_blockmask` allocates the eight arrays)."""
+    out = alloc_blockmask(bm.Bm, bm.Hm, bm.q_len, bm.kv_len, bm.Bq, bm.Bk, device=bm.kv_num_blocks.device)
+    for num, idx, fnum, fidx, onum, oidx, ofnum, ofidx in (
+            (bm.kv_num_blocks, bm.kv_indices, bm.full_kv_num_blocks, bm.full_kv_indices,
+             out.kv_num_blocks, out.kv_indices, out.full_kv_num_blocks, out.full_kv_indices),
+            (bm.q_num_blocks, bm.q_indices, bm.full_q_num_blocks, bm.full_q_indices,
+             out.q_num_blocks, out.q_indices, out.full_q_num_blocks, out.full_q_indices)):
+        n = idx.shape[-1]
+        pos = torch.arange(n, device=idx.device)
+        big = torch.iinfo(torch.int32).max
+        a = torch.where(pos < num.unsqueeze(-1), idx, big)
+        b = torch.where(pos < fnum.unsqueeze(-1), fidx, big)
+        merged = torch.sort(torch.cat([a, b], dim=-1), dim=-1).values[..., :n]
+        total = num + fnum
+        oidx.copy_(torch.where(pos < total.unsqueeze(-1), merged, 0).to(torch.int32))
+        onum.copy_(total)
+        ofnum.zero_()
+        ofidx.zero_()
+    if bm.stats is not None and out.stats is not None:
+        out.stats.copy_(bm.stats)
+    return out

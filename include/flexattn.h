@@ -159,6 +159,19 @@ typedef struct flexattn_blockmask {
     int32_t* full_q_indices;
 } flexattn_blockmask;
 
+/* Geometry and element counts of the eight arrays of a BlockMask (section 4.2), so that a caller
+ * can allocate them without repeating the library's rounding: NR = ceil(q_len / Bq),
+ * NC = ceil(kv_len / Bk); counts are in int32 elements, in the order of flexattn_blockmask.
+ * Host-only arithmetic.  FLEXATTN_ERR_INVALID_ARG for a non-positive argument or a NULL `sizes`,
+ * FLEXATTN_ERR_UNSUPPORTED if Bm * Hm * NR * NC exceeds 2^31 (the limit of flexattn_blockmask_build). */
+typedef struct flexattn_blockmask_counts {
+    int32_t NR, NC;
+    int64_t kv_num_blocks, kv_indices, full_kv_num_blocks, full_kv_indices;
+    int64_t q_num_blocks, q_indices, full_q_num_blocks, full_q_indices;
+} flexattn_blockmask_counts;
+int flexattn_blockmask_sizes(int32_t Bm, int32_t Hm, int32_t q_len, int32_t kv_len, int32_t Bq, int32_t Bk,
+                                flexattn_blockmask_counts* sizes);
+
 /* Problem shape of flex_attention (section 2.1). */
 typedef struct flexattn_dims {
     int32_t B, Hq, Hkv, q_len, kv_len, D;
@@ -168,7 +181,12 @@ const char* flexattn_strerror(int status);
 int         flexattn_last_hip_error(void);
 int         flexattn_version(void);
 
-/* 1 if forward/backward kernels for this (mask, score, D) were compiled into the library. */
+/* 1 if forward/backward kernels for this (mask, score, D) were compiled into the library.
+ * The BlockMask builder accepts every mask listed above; forward and backward are template
+ * instantiations over a table of (mask_id, score_id) pairs (csrc/flex_common.h,
+ * FLEXATTN_FOR_EACH_VARIANT): the pairs of the paper's examples and benchmarks.  The mask and score
+ * functors compose freely, so another pair is one more line in that table and a rebuild; a pair
+ * that is not in it is refused with FLEXATTN_ERR_UNSUPPORTED, never approximated. */
 int flexattn_is_supported(uint32_t mask_id, uint32_t score_id, int32_t D);
 
 /* ---- BlockMask construction (section 4.2; create_block_mask, section 1.1) ----------
@@ -303,7 +321,13 @@ int flexattn_paged_forward(const flexattn_dims* dims, const flexattn_tensor* Q,
  *   ctx_lens   [nseq] int32: visible keys are kv_idx < ctx_lens[b] (0 is legal: O = 0,
  *              LSE = -inf).  score_mods see q_idx = ctx_lens[b] - 1 and the LOGICAL kv_idx.
  *   O [nseq, Hq, D] bf16 dense; LSE nullable [nseq, Hq] fp32.
- * page_size must be 16, 32, 64 or 128; Hq / Hkv <= 16.  mask_id: FLEXATTN_MASK_CTX_LEN (which, with the query at
+ * page_size must be a power of two from 16 to 1024; Hq / Hkv <= 16; max_pages * page_size <= 2^30.
+ * Device-side values are not trusted: a context length outside [0, max_pages * page_size] is clamped to
+ * that range and a page id outside [0, n_pool_pages) to the nearest valid page, so that wrong tables
+ * give wrong rows and never an access outside the table, the pools or the workspace.
+ * The KV range is cut into splits of 128 ... 1024 keys, one wave each; the split length is chosen
+ * from nseq * Hkv * max_pages * page_size so that the launch still fills the chip when the batch is
+ * small (flexattn_paged_decode_workspace_bytes accounts for it).  mask_id: FLEXATTN_MASK_CTX_LEN (which, with the query at
  * q_idx = ctx_len - 1, is also the causal mask of a decode step: the offset conversion of section 5.2) or
  * FLEXATTN_MASK_CTX_LEN_WINDOW (additionally q_idx - kv_idx <= params->window; splits wholly below the
  * window are skipped).

@@ -71,6 +71,12 @@ class _BlockMask(C.Structure):
                 ("full_q_num_blocks", C.c_void_p), ("full_q_indices", C.c_void_p)]
 
 
+class _BlockMaskSizes(C.Structure):
+    _fields_ = [("NR", C.c_int32), ("NC", C.c_int32)] + [(n, C.c_int64) for n in (
+        "kv_num_blocks", "kv_indices", "full_kv_num_blocks", "full_kv_indices",
+        "q_num_blocks", "q_indices", "full_q_num_blocks", "full_q_indices")]
+
+
 class _Dims(C.Structure):
     _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("q_len", C.c_int32),
                 ("kv_len", C.c_int32), ("D", C.c_int32)]
@@ -100,6 +106,8 @@ def _lib():
     lib.flexattn_version.restype = C.c_int
     lib.flexattn_is_supported.restype = C.c_int
     lib.flexattn_is_supported.argtypes = [C.c_uint32, C.c_uint32, C.c_int32]
+    lib.flexattn_blockmask_sizes.restype = C.c_int
+    lib.flexattn_blockmask_sizes.argtypes = [C.c_int32] * 6 + [P(_BlockMaskSizes)]
     lib.flexattn_blockmask_workspace_bytes.restype = C.c_size_t
     lib.flexattn_blockmask_workspace_bytes.argtypes = [C.c_int32] * 6
     lib.flexattn_blockmask_build.restype = C.c_int
@@ -236,15 +244,27 @@ def _dims(Q: torch.Tensor, K: torch.Tensor) -> _Dims:
     return _Dims(Q.shape[0], Q.shape[1], K.shape[1], Q.shape[2], K.shape[2], Q.shape[3])
 
 
+def flexattn_blockmask_sizes(Bm: int, Hm: int, q_len: int, kv_len: int, Bq: int, Bk: int) -> _BlockMaskSizes:
+    sizes = _BlockMaskSizes()
+    _check(_lib().flexattn_blockmask_sizes(Bm, Hm, q_len, kv_len, Bq, Bk, C.byref(sizes)),
+           "flexattn_blockmask_sizes")
+    return sizes
+
+
 def alloc_blockmask(Bm: int, Hm: int, q_len: int, kv_len: int, Bq: int, Bk: int, device="cuda") -> BlockMask:
-    """Caller-side allocation of the eight int32 arrays (the library allocates nothing)."""
-    NR, NC = -(-q_len // Bq), -(-kv_len // Bk)       # the last block may be cut by the edge
+    """Caller-side allocation of the eight int32 arrays (the library allocates nothing), sized by
+    flexattn_blockmask_sizes and viewed as [Bm, Hm, NR(, NC)] / [Bm, Hm, NC(, NR)]."""
+    sz = flexattn_blockmask_sizes(Bm, Hm, q_len, kv_len, Bq, Bk)
     i32 = dict(dtype=torch.int32, device=device)
+
+    def arr(count, *shape):
+        return torch.empty(count, **i32).view(Bm, Hm, *shape)
+
     return BlockMask(Bm, Hm, q_len, kv_len, Bq, Bk,
-                     torch.empty(Bm, Hm, NR, **i32), torch.empty(Bm, Hm, NR, NC, **i32),
-                     torch.empty(Bm, Hm, NR, **i32), torch.empty(Bm, Hm, NR, NC, **i32),
-                     torch.empty(Bm, Hm, NC, **i32), torch.empty(Bm, Hm, NC, NR, **i32),
-                     torch.empty(Bm, Hm, NC, **i32), torch.empty(Bm, Hm, NC, NR, **i32),
+                     arr(sz.kv_num_blocks, sz.NR), arr(sz.kv_indices, sz.NR, sz.NC),
+                     arr(sz.full_kv_num_blocks, sz.NR), arr(sz.full_kv_indices, sz.NR, sz.NC),
+                     arr(sz.q_num_blocks, sz.NC), arr(sz.q_indices, sz.NC, sz.NR),
+                     arr(sz.full_q_num_blocks, sz.NC), arr(sz.full_q_indices, sz.NC, sz.NR),
                      torch.empty(4, dtype=torch.int64, device=device))
 
 

@@ -136,6 +136,22 @@ static int launch_classify(const flexattn_mod_params& p, const flexattn_blockmas
 
 using namespace flexattn;
 
+extern "C" int flexattn_blockmask_sizes(int32_t Bm, int32_t Hm, int32_t q_len, int32_t kv_len, int32_t Bq,
+                                           int32_t Bk, flexattn_blockmask_counts* sizes) {
+    if (!sizes || Bm <= 0 || Hm <= 0 || q_len <= 0 || kv_len <= 0 || Bq <= 0 || Bk <= 0)
+        return FLEXATTN_ERR_INVALID_ARG;
+    const int64_t NR = ((int64_t)q_len + Bq - 1) / Bq, NC = ((int64_t)kv_len + Bk - 1) / Bk;
+    const int64_t planes = (int64_t)Bm * Hm;
+    if (planes * NR * NC > (1ll << 31)) return FLEXATTN_ERR_UNSUPPORTED;
+    sizes->NR = (int32_t)NR;
+    sizes->NC = (int32_t)NC;
+    sizes->kv_num_blocks = sizes->full_kv_num_blocks = planes * NR;
+    sizes->kv_indices = sizes->full_kv_indices = planes * NR * NC;
+    sizes->q_num_blocks = sizes->full_q_num_blocks = planes * NC;
+    sizes->q_indices = sizes->full_q_indices = planes * NC * NR;
+    return FLEXATTN_OK;
+}
+
 extern "C" size_t flexattn_blockmask_workspace_bytes(int32_t Bm, int32_t Hm, int32_t q_len, int32_t kv_len,
                                                      int32_t Bq, int32_t Bk) {
     if (Bm <= 0 || Hm <= 0 || q_len <= 0 || kv_len <= 0 || Bq <= 0 || Bk <= 0) return 0;

@@ -18,7 +18,9 @@ namespace flexattn {
 
 constexpr int kDecWaves = 4;       // waves per workgroup (the mapping below assumes 4)
 constexpr int kDecTile = 32;       // keys per inner tile
-constexpr int kDecSplit = 1024;    // keys per split
+constexpr int kDecSplitMax = 1024; // keys per split: a power of two in [kDecSplitMin, kDecSplitMax],
+constexpr int kDecSplitMin = 128;  // chosen by the host so that the launch fills the chip (split_len_of)
+constexpr int kDecResidentWaves = 256 * 8;   // waves the chip holds at once: 256 CUs x 2 workgroups x 4
 
 struct DecodeArgs {
     const bf16* Q;
@@ -29,6 +31,9 @@ struct DecodeArgs {
     int64_t pt_stride;
     const int32_t* ctx_lens;
     int nseq, Hq, Hkv, G, page_size, page_shift, max_splits;
+    int split_len;       // keys per split
+    int max_ctx;         // max_pages * page_size: context lengths are clamped to what the page table can address
+    int n_pool_pages;    // page ids are clamped to [0, n_pool_pages)
     int window;          // sliding window (q_idx - kv <= window), -1 if none
     float scale;
     flexattn_mod_params p;
@@ -57,13 +62,16 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
     const int unit = blockIdx.x * upw + wave / spw;
     if (unit >= a.nseq * a.Hkv || split >= a.max_splits) return;
     const int b = unit / a.Hkv, hkv = unit % a.Hkv;
-    const int ctx = a.ctx_lens[b];
+    // A context length beyond what the page table addresses (or a negative one) is clamped, and so is
+    // every page id below: wrong device-side tables give wrong rows, never an access outside the
+    // table, the pools or the workspace.
+    const int ctx = min(max(a.ctx_lens[b], 0), a.max_ctx);
     // The query sits at q_idx = ctx - 1 (the offset of the decode step), so "causal" is kv < ctx and a
     // sliding window adds the lower bound kv >= q_idx - window.
     const int kv_lo = a.window >= 0 ? max(ctx - 1 - a.window, 0) : 0;
-    const int tok_begin = split * kDecSplit;
-    if (tok_begin >= ctx || tok_begin + kDecSplit <= kv_lo) return;   // wave-uniform; the kernel has no barriers
-    const int tok_end = min(ctx, tok_begin + kDecSplit);
+    const int tok_begin = split * a.split_len;
+    if (tok_begin >= ctx || tok_begin + a.split_len <= kv_lo) return;   // wave-uniform; the kernel has no barriers
+    const int tok_end = min(ctx, tok_begin + a.split_len);
     const int tok_first = max(tok_begin, kv_lo & ~(kDecTile - 1));    // first tile that holds a visible key
     bf16* k_tile = smem + wave * 2 * TILE;
     bf16* v_tile = k_tile + TILE;
@@ -102,7 +110,7 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int tok = min(tok0 + i * RPI + lane / DC, ctx - 1);
-            pg[i] = pt[tok >> a.page_shift];
+            pg[i] = min(max(pt[tok >> a.page_shift], 0), a.n_pool_pages - 1);
         }
     };
     // Gather of the 32 K rows and 32 V rows of a tile through the page table, straight into LDS.  The
@@ -217,9 +225,9 @@ template <int D>
 __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) {
     const int lane = threadIdx.x;
     const int b = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq;
-    const int ctx = a.ctx_lens[b];
-    const int ns = (ctx + kDecSplit - 1) / kDecSplit;
-    const int s0 = a.window >= 0 ? max(ctx - 1 - a.window, 0) / kDecSplit : 0;     // splits below the window are empty
+    const int ctx = min(max(a.ctx_lens[b], 0), a.max_ctx);                          // as in the split kernel
+    const int ns = (ctx + a.split_len - 1) / a.split_len;                           // <= max_splits
+    const int s0 = a.window >= 0 ? max(ctx - 1 - a.window, 0) / a.split_len : 0;    // splits below the window are empty
     const int64_t base = ((int64_t)b * a.Hq + hq) * a.max_splits;
     bf16* o = a.O + ((int64_t)b * a.Hq + hq) * D;
     constexpr int PER = D / 64;
@@ -247,9 +255,23 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
     if (lane == 0 && a.LSE) a.LSE[(int64_t)b * a.Hq + hq] = (m + fast_log2(L)) * kLn2;
 }
 
+// Keys per split.  One wave works on one (sequence, KV head, split), so a launch offers
+// nseq * Hkv * ceil(ctx / split_len) waves; the host cannot see the context lengths and sizes the
+// split for the longest context the page table addresses: the largest power of two in
+// [kDecSplitMin, kDecSplitMax] that still gives the chip one wave per slot, so that a small batch
+// of long sequences is cut finer than a large one.
+static int split_len_of(const flexattn_decode_dims* d) {
+    const long long max_tokens = (long long)d->max_pages * d->page_size;
+    const long long per_wave = max_tokens * d->nseq * d->Hkv / kDecResidentWaves;
+    int len = kDecSplitMin;
+    while (len < kDecSplitMax && 2 * len <= per_wave) len *= 2;
+    return len;
+}
+
 static int max_splits_of(const flexattn_decode_dims* d) {
     const long long max_tokens = (long long)d->max_pages * d->page_size;
-    return (int)((max_tokens + kDecSplit - 1) / kDecSplit);
+    const int len = split_len_of(d);
+    return (int)((max_tokens + len - 1) / len);
 }
 
 template <int D>
@@ -283,8 +305,9 @@ static int check_decode_dims(const flexattn_decode_dims* d) {
     if (d->Hq % d->Hkv != 0) return FLEXATTN_ERR_INVALID_ARG;
     if (d->D != 64 && d->D != 128) return FLEXATTN_ERR_UNSUPPORTED;
     if (d->Hq / d->Hkv > 16) return FLEXATTN_ERR_UNSUPPORTED;
-    if (d->page_size != 16 && d->page_size != 32 && d->page_size != 64 && d->page_size != 128)
+    if (d->page_size < 16 || d->page_size > 1024 || (d->page_size & (d->page_size - 1)))
         return FLEXATTN_ERR_UNSUPPORTED;
+    if ((long long)d->max_pages * d->page_size > (1ll << 30)) return FLEXATTN_ERR_UNSUPPORTED;
     return FLEXATTN_OK;
 }
 
@@ -323,6 +346,9 @@ extern "C" int flexattn_paged_decode(const flexattn_decode_dims* d, const void* 
     a.page_size = d->page_size;
     a.page_shift = __builtin_ctz((unsigned)d->page_size);
     a.max_splits = max_splits_of(d);
+    a.split_len = split_len_of(d);
+    a.max_ctx = d->max_pages * d->page_size;
+    a.n_pool_pages = d->n_pool_pages;
     a.window = mask_id == kCtxWindow ? p.window : -1;
     a.scale = scale; a.p = p;
     const size_t items = (size_t)d->nseq * d->Hq * a.max_splits;

@@ -101,3 +101,37 @@ def test_product_does_not_import_oracle():
             if f.endswith((".py", ".h", ".hip", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.replace("no CPU fallback", ""), f
+
+
+def test_blockmask_sizes_is_host_arithmetic():
+    lib = binding._lib()
+    sz = binding._BlockMaskSizes()
+    assert lib.flexattn_blockmask_sizes(2, 3, 1000, 517, 128, 64, C.byref(sz)) == fa.OK
+    NR, NC = 8, 9                                     # ceil(1000 / 128), ceil(517 / 64)
+    assert (sz.NR, sz.NC) == (NR, NC)
+    assert sz.kv_num_blocks == sz.full_kv_num_blocks == 6 * NR
+    assert sz.kv_indices == sz.full_kv_indices == 6 * NR * NC
+    assert sz.q_num_blocks == sz.full_q_num_blocks == 6 * NC
+    assert sz.q_indices == sz.full_q_indices == 6 * NC * NR
+    assert lib.flexattn_blockmask_sizes(1, 1, 0, 64, 64, 64, C.byref(sz)) == fa.ERR_INVALID_ARG
+    assert lib.flexattn_blockmask_sizes(1, 1, 64, 64, 64, 64, None) == fa.ERR_INVALID_ARG
+    assert lib.flexattn_blockmask_sizes(64, 64, 1 << 20, 1 << 20, 64, 64, C.byref(sz)) == fa.ERR_UNSUPPORTED
+    # the workspace of the builder is one byte per block, rounded up to 256
+    assert lib.flexattn_blockmask_workspace_bytes(2, 3, 1000, 517, 128, 64) == (6 * NR * NC + 255) // 256 * 256
+
+
+def test_decode_workspace_follows_the_split_length():
+    """Splits are 1024 keys when nseq * Hkv * (addressable context) fills the chip that way, and
+    shorter (down to 128) for small batches; the workspace holds D + 2 floats per (seq, head, split)."""
+    lib = binding._lib()
+
+    def ws(nseq, Hq, Hkv, D, page, max_pages):
+        d = binding._DecodeDims(nseq, Hq, Hkv, D, page, max_pages, 1)
+        return lib.flexattn_paged_decode_workspace_bytes(C.byref(d))
+
+    assert ws(64, 32, 8, 128, 16, 2048) == 64 * 32 * 32 * 130 * 4          # config 5: 32 splits of 1024
+    assert ws(1, 32, 8, 128, 16, 512) == 1 * 32 * 64 * 130 * 4             # 8192 tokens, 8 heads: 128-key splits
+    assert ws(4, 8, 8, 64, 256, 128) == 4 * 8 * 64 * 66 * 4                # 32768 tokens x 32 units: 512-key splits
+    assert ws(2, 4, 2, 64, 16, 4) == 2 * 4 * 1 * 66 * 4                    # shorter than one split
+    assert ws(2, 4, 2, 64, 24, 4) == 0 and ws(2, 4, 2, 64, 2048, 4) == 0   # page sizes that are refused
+    assert ws(2, 4, 2, 64, 8, 4) == 0

@@ -35,10 +35,13 @@ def test_captured_gradients_match_oracle(case):
     for _ in range(2):      # written, not accumulated: a second call gives the same
         fa.flexattn_backward_captured(Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, d_alibi, d_rel)
     torch.cuda.synchronize()
+    # These sums run over EVERY (q, kv) pair of a head (the ALiBi one weighted by q - kv), so the
+    # rounding of delta = rowsum(dO * O) from the bf16 O, which shifts all dS of a row the same way,
+    # does not average out as it does in dQ / dK / dV: mean error <= 1e-2 of the mean magnitude.
     if d_alibi is not None:
-        hp.check_grad("d_alibi_bias", d_alibi, ref["alibi_bias"])
+        hp.check_grad("d_alibi_bias", d_alibi, ref["alibi_bias"], mean_tol=1e-2)
     if d_rel is not None:
-        hp.check_grad("d_rel_bias", d_rel, ref["rel_bias"])
+        hp.check_grad("d_rel_bias", d_rel, ref["rel_bias"], mean_tol=1e-2)
         assert float(ref["rel_bias"].abs().max()) > 0
 
 

@@ -42,7 +42,8 @@ def test_ragged_lengths_and_edge_cases():
     compare(inp, O, LSE, fo.Identity())
 
 
-@pytest.mark.parametrize("D,G,page", [(128, 4, 16), (64, 1, 16), (128, 8, 64), (64, 4, 128)])
+@pytest.mark.parametrize("D,G,page", [(128, 4, 16), (64, 1, 16), (128, 4, 32), (64, 2, 32), (128, 8, 64), (64, 4, 128),
+                                      (128, 4, 256), (64, 2, 256), (128, 2, 512)])
 def test_shapes_and_page_sizes(D, G, page):
     wl = wlm.CFG5.scaled(B=6, Hq=2 * G, Hkv=2, D=D, page_size=page, ctx_min=1, ctx_max=3000,
                          max_pages=(3000 + page - 1) // page + 1)
@@ -79,6 +80,61 @@ def test_score_mods_in_decode():
     slopes = wlm.alibi_slopes(8)
     O, LSE = run_decode(inp, fa.SCORE_ALIBI, fa.ModParams(alibi_bias=(-slopes).to(DEV)))
     compare(inp, O, LSE, fo.Alibi(-slopes.double()))
+
+
+def test_relative_bias_in_decode():
+    import paper_2412_05496_amd as fa
+    wl = wlm.CFG5.scaled(B=5, Hq=8, Hkv=2, ctx_min=50, ctx_max=2500, max_pages=160)
+    inp = wlm.make_decode_inputs(wl)
+    table = torch.randn(8, 256, generator=torch.Generator().manual_seed(9)) * 0.5
+    O, LSE = run_decode(inp, fa.SCORE_REL_BIAS, fa.ModParams(rel_bias=table.to(DEV)))
+    compare(inp, O, LSE, fo.RelBias(table.double()))
+
+
+@pytest.mark.parametrize("nseq,Hkv,ctx_max", [(1, 8, 8192), (2, 1, 20000), (3, 2, 700)])
+def test_small_batches_are_cut_into_short_splits(nseq, Hkv, ctx_max):
+    """The split length follows nseq * Hkv * (longest addressable context), so a small batch is cut into
+    128 ... 512-key splits and a (sequence, head) is combined from many more partials than config 5's."""
+    wl = wlm.CFG5.scaled(B=nseq, Hq=4 * Hkv, Hkv=Hkv, ctx_min=max(ctx_max - 300, 1), ctx_max=ctx_max,
+                         max_pages=(ctx_max + 15) // 16)
+    inp = wlm.make_decode_inputs(wl, slack_pages=2)
+    print(f"[case] small batch nseq={nseq} Hkv={Hkv} ctx={inp.ctx_lens.tolist()}", flush=True)
+    O, LSE = run_decode(inp)
+    compare(inp, O, LSE, fo.Identity())
+
+
+def test_wrong_tables_never_leave_the_buffers():
+    """Device-side values are not trusted: page ids outside the pool and context lengths beyond what the
+    page table addresses (or negative) are clamped, so the call returns normally with finite numbers --
+    wrong rows, never an access outside the table, the pools or the workspace."""
+    wl = wlm.CFG5.scaled(B=6, Hq=8, Hkv=2, ctx_min=100, ctx_max=1500, max_pages=96)
+    inp = wlm.make_decode_inputs(wl, slack_pages=1)
+    good_O, good_LSE = run_decode(inp)
+    pt = inp.page_table.clone()
+    pt[0, 0] = 2 ** 30                      # far past the pool
+    pt[1, 1] = -7                           # negative
+    pt[2, :] = inp.K_pool.shape[0]          # one past the last page, everywhere
+    ctx = inp.ctx_lens.clone()
+    ctx[3] = 96 * 16 + 5000                 # longer than the page table can address
+    ctx[4] = -3                             # negative: treated as empty
+    bad = wlm.DecodeInputs(wl, inp.Q, inp.K_pool, inp.V_pool, pt.contiguous(), ctx.contiguous(), inp.scale)
+    O, LSE = run_decode(bad)
+    assert torch.isfinite(O.float()).all()
+    assert torch.isfinite(LSE[[0, 1, 2, 3, 5]]).all()
+    assert (O[4] == 0).all() and torch.isinf(LSE[4]).all()
+    # the untouched sequence is unaffected, bit for bit
+    assert torch.equal(O[5], good_O[5]) and torch.equal(LSE[5], good_LSE[5])
+    # a clamped id reads the nearest valid page: the same result as a table that names that page
+    fixed = pt.clone()
+    fixed[0, 0] = inp.K_pool.shape[0] - 1
+    fixed[1, 1] = 0
+    fixed[2, :] = inp.K_pool.shape[0] - 1
+    ctx_fixed = ctx.clone()
+    ctx_fixed[3] = 96 * 16
+    ctx_fixed[4] = 0
+    O2, LSE2 = run_decode(wlm.DecodeInputs(wl, inp.Q, inp.K_pool, inp.V_pool, fixed.contiguous(),
+                                           ctx_fixed.contiguous(), inp.scale))
+    assert torch.equal(O, O2) and torch.equal(LSE, LSE2)
 
 
 def test_full_config5():

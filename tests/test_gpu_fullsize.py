@@ -81,3 +81,4 @@ def test_cfg4_swa_prefix_relbias_gqa_full_size():
     check_full_size(wl, heads=[(0, 0), (1, 13), (1, 31)], n_rows=24,
                     col_groups=[(0, 2, torch.arange(wl.S - 96, wl.S)), (1, 7, torch.arange(20000, 20032)),
                                 (0, 0, torch.arange(1024, 1032))])
+

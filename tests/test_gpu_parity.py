@@ -1,7 +1,9 @@
 """GPU parity: the HIP path (through the C ABI) against the fp64 oracle on identical seeded inputs.
 
 BlockMask arrays must match bit for bit.  O (bf16) vs oracle: max abs <= 2e-2, mean abs <= 2e-3;
-LSE <= 1e-2; gradients: max abs <= 2e-2 * max(1, max|ref|), mean abs <= 2e-3 * max(1, 10 mean|ref|).
+LSE <= 1e-2; gradients: max abs <= 2e-2 * max(1, max|ref|), mean abs <= 6e-3 * max(1, mean|ref|), and no
+more than 3x (max) / 1.5x (mean) the error of an emulation that rounds only what a bf16 matrix-unit kernel must round
+(helpers.check_grad, helpers.emulate_bf16_backward).
 """
 import pytest
 import torch
@@ -9,8 +11,8 @@ import torch
 import flex_workloads as wlm
 from oracle import flex_oracle as fo
 
-from helpers import (assert_blockmask_equal, check_grad, check_output, library_mods, oracle_mods, run_backward,
-                     run_forward)
+from helpers import (assert_blockmask_equal, check_grad, check_output, emulate_bf16_backward, library_mods,
+                     oracle_mods, run_backward, run_forward)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -59,22 +61,58 @@ def test_forward_backward_small(name):
     check_output(O, LSE, O_ref, LSE_ref)
     dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids)
     dQ_ref, dK_ref, dV_ref = fo.flex_attention_backward(inp.Q, inp.K, inp.V, inp.dO, score, mask, inp.scale)
-    check_grad("dQ", dQ, dQ_ref)
-    check_grad("dK", dK, dK_ref)
-    check_grad("dV", dV, dV_ref)
+    dQ_em, dK_em, dV_em = emulate_bf16_backward(inp, score, mask)
+    check_grad("dQ", dQ, dQ_ref, dQ_em)
+    check_grad("dK", dK, dK_ref, dK_em)
+    check_grad("dV", dV, dV_ref, dV_em)
+
+
+# One BlockMask plane per query head (Hm = Hq): the kernels index the lists by the QUERY head, also
+# under GQA where several query heads share a KV head (dK / dV walk one transposed list per head).
+PER_HEAD = {
+    "causal_softcap_d128_gqa": wlm.Workload("ph128", B=2, Hq=4, Hkv=2, S=640, D=128, Bq=128, Bk=64, mask="causal",
+                                            score="softcap", seed=31, softcap=30.0),
+    "swa_prefix_relbias_d64_gqa": wlm.Workload("ph64", B=1, Hq=6, Hkv=2, S=768, D=64, Bq=64, Bk=128,
+                                               mask="swa_causal_or_prefix", score="rel_bias", seed=32, window=150,
+                                               prefix_len=70, rel_len=64),
+    "doc_alibi_d64": wlm.Workload("phdoc", B=2, Hq=4, Hkv=4, S=512, D=64, Bq=128, Bk=64, mask="doc_causal",
+                                  score="alibi", seed=33, doc_len_min=40, doc_len_max=300),
+}
+
+
+@pytest.mark.parametrize("name", list(PER_HEAD))
+def test_per_head_blockmask(name):
+    wl = PER_HEAD[name]
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    score, mask = oracle_mods(wl, inp)
+    print(f"[case] per-head BlockMask {name} {wl}", flush=True)
+    O, LSE, bm, ids = run_forward(wl, inp, DEV, Hm=wl.Hq)
+    assert bm.Hm == wl.Hq and bm.kv_indices.shape[1] == wl.Hq
+    assert_blockmask_equal(bm, fo.create_block_mask(mask, bm.Bm, wl.Hq, wl.S, wl.S, wl.Bq, wl.Bk))
+    O_ref, LSE_ref = fo.flex_attention(inp.Q, inp.K, inp.V, score, mask, inp.scale)
+    check_output(O, LSE, O_ref, LSE_ref)
+    dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids)
+    g_ref = fo.flex_attention_backward(inp.Q, inp.K, inp.V, inp.dO, score, mask, inp.scale)
+    g_em = emulate_bf16_backward(inp, score, mask)
+    for n, g, r, e in zip(("dQ", "dK", "dV"), (dQ, dK, dV), g_ref, g_em):
+        check_grad(n, g, r, e)
+    # the same call with the shared plane must give the same bits: the planes are identical
+    O1, LSE1, bm1, _ = run_forward(wl, inp, DEV)
+    assert torch.equal(O, O1) and torch.equal(LSE, LSE1)
+    for a, b1 in zip((dQ, dK, dV), run_backward(wl, inp, DEV, O1, LSE1, bm1, ids)):
+        assert torch.equal(a, b1)
 
 
 def test_blockmask_without_full_blocks_gives_the_same_attention():
     """Listing every FULL block as PARTIAL (mask_mod evaluated everywhere, paper section 4.2) must not change
     the result beyond rounding: the tiles are merely visited in another order."""
-    import bench_sweep
     import paper_2412_05496_amd as fa
     wl = SMALL["cfg2_small"]
     inp = wlm.make_train_inputs(wl, with_dO=True)
     score, mask = oracle_mods(wl, inp)
     O, LSE, bm, ids = run_forward(wl, inp, DEV)
     mask_id, score_id, params, Q, K, V = ids
-    bm2 = bench_sweep.all_partial(fa, bm)
+    bm2 = wlm.blockmask_all_partial(fa.alloc_blockmask, bm)
     assert int(bm2.full_kv_num_blocks.sum()) == 0 and int(bm2.full_q_num_blocks.sum()) == 0
     assert torch.equal(bm2.kv_num_blocks, bm.kv_num_blocks + bm.full_kv_num_blocks)
     O2, LSE2 = torch.empty_like(O), torch.empty_like(LSE)
@@ -166,3 +204,35 @@ def test_backward_strided_layout_and_stages_agree():
                                     dVs if stage == fa.BWD_DKDV else None, ws, stage)
     torch.cuda.synchronize()
     assert torch.equal(dQs, dQ) and torch.equal(dKs, dK) and torch.equal(dVs, dV)
+
+
+@pytest.mark.parametrize("mask_name", ["causal", "none"])
+def test_dkdv_walk_longer_than_one_segment(mask_name):
+    """A key column seen by more row blocks than the 1024 steps the dK/dV kernel lays out in LDS at a
+    time: q_len = 66 560 in 64-row blocks against 128 keys, so each of the two key columns lists 1040
+    (causal: 1 PARTIAL + 1039 FULL, resp. 1039 FULL) row blocks and the kernel walks them in two
+    segments.  With so few keys the oracle evaluates every element."""
+    import paper_2412_05496_amd as fa
+    B, H, Sq, Skv, D, Bq, Bk = 1, 1, 66560, 128, 64, 64, 64
+    gen = torch.Generator().manual_seed(41)
+    Q, dO = wlm.randn_bf16(gen, B, H, Sq, D), wlm.randn_bf16(gen, B, H, Sq, D)
+    K, V = wlm.randn_bf16(gen, B, H, Skv, D), wlm.randn_bf16(gen, B, H, Skv, D)
+    scale = D ** -0.5
+    mask_id, mask = {"causal": (fa.MASK_CAUSAL, fo.causal_mask), "none": (fa.MASK_NONE, fo.no_mask)}[mask_name]
+    params = fa.ModParams()
+    bm = fa.alloc_blockmask(1, 1, Sq, Skv, Bq, Bk, device=DEV)
+    fa.flexattn_blockmask_build(mask_id, params, bm)
+    assert_blockmask_equal(bm, fo.create_block_mask(mask, 1, 1, Sq, Skv, Bq, Bk))
+    assert int((bm.q_num_blocks + bm.full_q_num_blocks).max()) > 1024
+    Qd, Kd, Vd, dOd = (t.to(DEV) for t in (Q, K, V, dO))
+    O = torch.full_like(Qd, float("nan"))
+    LSE = torch.full((B, H, Sq), float("nan"), dtype=torch.float32, device=DEV)
+    fa.flexattn_forward(Qd, Kd, Vd, fa.SCORE_IDENTITY, mask_id, params, bm, scale, O, LSE)
+    dQ, dK, dV = (torch.full_like(t, float("nan")) for t in (Qd, Kd, Vd))
+    fa.flexattn_backward(Qd, Kd, Vd, O, dOd, LSE, fa.SCORE_IDENTITY, mask_id, params, bm, scale, dQ, dK, dV)
+    torch.cuda.synchronize()
+    O_ref, LSE_ref = fo.flex_attention(Q, K, V, fo.Identity(), mask, scale)
+    check_output(O, LSE, O_ref, LSE_ref)
+    g_ref = fo.flex_attention_backward(Q, K, V, dO, fo.Identity(), mask, scale)
+    for n, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), g_ref):
+        check_grad(n, g, r)
