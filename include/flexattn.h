@@ -345,6 +345,26 @@ int flexattn_paged_decode(const flexattn_decode_dims* dims,
                           float scale, void* O, float* LSE,
                           void* ws, size_t ws_bytes, void* stream);
 
+/* flexattn_paged_decode without a workspace argument, for callers that cannot allocate device
+ * memory: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * partial results live in an array inside the library's device image (one copy per GPU, held until
+ * the process ends) of flexattn_paged_decode_static_capacity() bytes = 40 MiB -- enough for 64
+ * sequences x 32 query heads x 32 splits at D = 128.  The call allocates and frees nothing; it
+ * returns FLEXATTN_ERR_WORKSPACE, launching nothing, when
+ * flexattn_paged_decode_workspace_bytes(dims) exceeds the capacity.  Arguments, results and every
+ * other error as flexattn_paged_decode (same kernels, bit-identical output).
+ * The FIRST call on each device looks the array's address up (hipGetSymbolAddress): make it before
+ * a capture begins.  All calls on one GPU share the array: calls that may overlap there (different
+ * streams, different threads) race -- serialise them or use flexattn_paged_decode with separate
+ * workspaces.  Nothing in the array needs clearing between calls. */
+size_t flexattn_paged_decode_static_capacity(void);
+int flexattn_paged_decode_static(const flexattn_decode_dims* dims,
+                                 const void* Q, int64_t stride_q_seq,
+                                 const void* K_pool, const void* V_pool,
+                                 const int32_t* page_table, int64_t pt_stride, const int32_t* ctx_lens,
+                                 uint32_t score_id, uint32_t mask_id, const flexattn_mod_params* params,
+                                 float scale, void* O, float* LSE, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -145,6 +145,10 @@ def _lib():
                                           C.c_void_p, C.c_int64, C.c_void_p, C.c_uint32, C.c_uint32,
                                           P(_ModParams), C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+    lib.flexattn_paged_decode_static_capacity.restype = C.c_size_t
+    lib.flexattn_paged_decode_static_capacity.argtypes = []
+    lib.flexattn_paged_decode_static.restype = C.c_int
+    lib.flexattn_paged_decode_static.argtypes = lib.flexattn_paged_decode.argtypes[:14] + [C.c_void_p]
     _handle = lib
     return lib
 
@@ -402,4 +406,21 @@ def flexattn_paged_decode(Q, K_pool, V_pool, page_table, ctx_lens, score_id: int
                                         page_table.data_ptr(), page_table.stride(0), ctx_lens.data_ptr(), score_id,
                                         mask_id, C.byref(p), scale, O.data_ptr(), _ptr(LSE), ws.data_ptr(),
                                         ws.numel(), _stream()), "flexattn_paged_decode")
+    return O, LSE
+
+
+def flexattn_paged_decode_static_capacity() -> int:
+    return _lib().flexattn_paged_decode_static_capacity()
+
+
+def flexattn_paged_decode_static(Q, K_pool, V_pool, page_table, ctx_lens, score_id: int, mask_id: int,
+                                 params: ModParams, scale: float, O, LSE=None):
+    """flexattn_paged_decode on the library's own static workspace (nothing is allocated)."""
+    assert K_pool.is_contiguous() and V_pool.is_contiguous() and O.is_contiguous()
+    assert Q.stride(-1) == 1 and Q.stride(1) == Q.shape[-1]
+    d, p = _decode_dims(Q, K_pool, page_table), params._c()
+    _check(_lib().flexattn_paged_decode_static(C.byref(d), Q.data_ptr(), Q.stride(0), K_pool.data_ptr(),
+                                               V_pool.data_ptr(), page_table.data_ptr(), page_table.stride(0),
+                                               ctx_lens.data_ptr(), score_id, mask_id, C.byref(p), scale,
+                                               O.data_ptr(), _ptr(LSE), _stream()), "flexattn_paged_decode_static")
     return O, LSE

@@ -11,8 +11,16 @@
 // operand, so K and V are read once per KV head, never once per query head; V^T comes out of the
 // row-major V tile through the transposing LDS read.  Each wave leaves (m, l, O) of its split in
 // the workspace; the combine kernel merges the splits of a (sequence, head) with log-sum-exp weights.
+#include <mutex>
+
 #include "flex_common.h"
 #include "lds_tiles.h"
+
+// Workspace of flexattn_paged_decode_static(): lives in the library's device image, one copy per
+// GPU, for callers that cannot allocate.  In host code this name is only a handle for
+// hipGetSymbolAddress(); kernels receive the device address it returns, like any other workspace.
+constexpr size_t kStaticScratchBytes = (size_t)40 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace flexattn {
 
@@ -315,6 +323,43 @@ extern "C" size_t flexattn_paged_decode_workspace_bytes(const flexattn_decode_di
     if (check_decode_dims(d) != FLEXATTN_OK) return 0;
     const size_t items = (size_t)d->nseq * d->Hq * max_splits_of(d);
     return items * ((size_t)d->D + 2) * sizeof(float);
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* addr[kMaxDevices] = {};
+    int dev = -1;
+    FLEXATTN_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return FLEXATTN_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        FLEXATTN_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return FLEXATTN_ERR_HIP;
+        addr[dev] = p;
+    }
+    *out = addr[dev];
+    return FLEXATTN_OK;
+}
+
+extern "C" size_t flexattn_paged_decode_static_capacity(void) { return kStaticScratchBytes; }
+
+extern "C" int flexattn_paged_decode_static(const flexattn_decode_dims* d, const void* Q, int64_t stride_q_seq,
+                                            const void* K_pool, const void* V_pool, const int32_t* page_table,
+                                            int64_t pt_stride, const int32_t* ctx_lens, uint32_t score_id,
+                                            uint32_t mask_id, const flexattn_mod_params* params, float scale, void* O,
+                                            float* LSE, void* stream) {
+    int rc = check_decode_dims(d);
+    if (rc != FLEXATTN_OK) return rc;
+    // Every partial the combine kernel reads was written by the split kernel of the same call, so
+    // nothing in the array has to start at zero.
+    if (flexattn_paged_decode_workspace_bytes(d) > kStaticScratchBytes) return FLEXATTN_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws)) != FLEXATTN_OK) return rc;
+    return flexattn_paged_decode(d, Q, stride_q_seq, K_pool, V_pool, page_table, pt_stride, ctx_lens, score_id,
+                                 mask_id, params, scale, O, LSE, ws, kStaticScratchBytes, stream);
 }
 
 extern "C" int flexattn_paged_decode(const flexattn_decode_dims* d, const void* Q, int64_t stride_q_seq,
