@@ -9,7 +9,12 @@ the forward, 10*D for the backward (five GEMMs; recomputation is not credited).
 
 The JSON line also carries
   roofline      the longest kernel of the step against the dense bf16 MFMA peak, timed with
-                events on the launch stream;
+                events on the launch stream (`traffic` is the HBM byte count of that kernel from the
+                rocprofv3 --pmc runs recorded under profiles/, not a measurement of this run);
+  measured_peaks  what this chip sustains in this very run: an MFMA-only kernel and a plain
+                streaming read, so that every fraction can also be read against achievable rates;
+  cfg3, cfg4    forward and backward of the document-mask + ALiBi and the sliding-window/prefix +
+                relative-bias GQA workloads (outside the timed step), with the BlockMask density;
   decode        the paged split-KV decode workload (64 sequences, 16-token pages) in HBM GB/s of
                 algorithmic K+V bytes, with its own roofline object;
   cpu_baseline  the fp64 oracle timed on this host's cores on a bounded sample of the same workload.
@@ -53,6 +58,56 @@ def event_time_ms(fn, iters: int) -> float:
     return start.elapsed_time(stop) / iters
 
 
+def train_leg(fa, wlm, wl, dev, iters: int, mfma_tflops: float) -> dict:
+    """Forward and backward of one of the other training workloads: ms, TFLOP/s over unmasked FLOPs,
+    fractions of the datasheet and of the measured MFMA rate, BlockMask density."""
+    import torch
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    Q, Kt, V, dO = (t.to(dev) for t in (inp.Q, inp.K, inp.V, inp.dO))
+    note = None
+    if wl.mask == "doc_causal":
+        mask_id, score_id, Bm = fa.MASK_DOCUMENT_CAUSAL, fa.SCORE_ALIBI, wl.B
+        params = fa.ModParams(doc_ids=inp.doc_ids.to(dev), alibi_bias=(-inp.slopes).to(dev))
+        note = ("ALiBi slopes 2^(-8(h+1)/H), h = 0..H-1 (the usual 1-based reading of 2^(-8h/H)); documents: "
+                + ", ".join(str(n) for n in inp.doc_lengths[0]) + " tokens")
+    else:
+        mask_id, score_id, Bm = fa.MASK_SWA_CAUSAL_OR_PREFIX, fa.SCORE_REL_BIAS, 1
+        params = fa.ModParams(window=wl.window, prefix_len=wl.prefix_len, rel_bias=inp.rel_bias.to(dev))
+    bm = fa.alloc_blockmask(Bm, 1, wl.S, wl.S, wl.Bq, wl.Bk, device=dev)
+    fa.flexattn_blockmask_build(mask_id, params, bm)
+    O = torch.empty_like(Q)
+    LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=dev)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Kt), torch.empty_like(V)
+    ws = torch.empty(fa.flexattn_backward_workspace_bytes(Q, Kt), dtype=torch.uint8, device=dev)
+    fwd = lambda: fa.flexattn_forward(Q, Kt, V, score_id, mask_id, params, bm, inp.scale, O, LSE)
+    bwd = lambda st=fa.BWD_ALL: fa.flexattn_backward_stages(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm,
+                                                            inp.scale, dQ, dK, dV, ws, st)
+    fwd(), bwd()
+    torch.cuda.synchronize()
+    t_f, t_b = event_time_ms(fwd, iters), event_time_ms(bwd, iters)
+    t_dkdv = event_time_ms(lambda: bwd(fa.BWD_DKDV), iters)
+    t_dq = event_time_ms(lambda: bwd(fa.BWD_DQ), iters)
+    partial, full, total, unmasked = bm.stats.cpu().tolist()
+    pairs = unmasked * (wl.B // Bm) * wl.Hq
+    f_f, f_b = 4 * wl.D * pairs / (t_f * 1e-3) / 1e12, 10 * wl.D * pairs / (t_b * 1e-3) / 1e12
+    leg = {
+        "workload": wl.name, "pairs": pairs, "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4),
+        "bwd_dkdv_ms": round(t_dkdv, 4), "bwd_dq_ms": round(t_dq, 4),
+        "fwd_tflops": round(f_f, 1), "bwd_tflops": round(f_b, 1),
+        "fwd_frac_of_bf16_peak": round(f_f / PEAK_BF16_TFLOPS, 4),
+        "bwd_frac_of_bf16_peak": round(f_b / PEAK_BF16_TFLOPS, 4),
+        "fwd_frac_of_measured_mfma": round(f_f / mfma_tflops, 4),
+        "bwd_frac_of_measured_mfma": round(f_b / mfma_tflops, 4),
+        "blockmask": {"partial": partial, "full": full, "total": total,
+                      "block_density": round((partial + full) / total, 4),
+                      "element_density": round(unmasked / (Bm * wl.S * wl.S), 4),
+                      "executed_over_unmasked_pairs": round((partial + full) * wl.Bq * wl.Bk / unmasked, 4)},
+    }
+    if note:
+        leg["note"] = note
+    return leg
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -60,6 +115,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the cfg3 / cfg4 legs")
     ap.add_argument("--cpu-heads", type=int, default=12, help="(b, h) slices the oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for HBM byte counters)")
@@ -165,6 +221,34 @@ def main() -> int:
         "roofline": roofline,
     }
 
+    # ------------------------------------------------------------------ what the chip sustains
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    probe_iters = 20000
+    fa.flexattn_probe_mfma(200, sink)
+    mfma_ms = event_time_ms(lambda: fa.flexattn_probe_mfma(probe_iters, sink), 3)
+    mfma_tflops = fa.flexattn_probe_mfma_flops(probe_iters) / (mfma_ms * 1e-3) / 1e12
+    stream_src = torch.empty(4 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    fa.flexattn_probe_stream_read(stream_src, sink)
+    read_ms = event_time_ms(lambda: fa.flexattn_probe_stream_read(stream_src, sink), 5)
+    read_gbs = stream_src.numel() / (read_ms * 1e-3) / 1e9
+    del stream_src
+    out["measured_peaks"] = {
+        "mfma_bf16_tflops": round(mfma_tflops, 1), "stream_read_gbs": round(read_gbs, 1),
+        "how": "flexattn_probe_mfma (32x32x16 bf16 MFMAs on register operands, 2 waves per SIMD) and "
+               "flexattn_probe_stream_read (4 GiB, 16-byte loads), events on the launch stream",
+        "fwd_frac_of_measured_mfma": round(out["fwd_tflops"] / mfma_tflops, 4),
+        "bwd_frac_of_measured_mfma": round(out["bwd_tflops"] / mfma_tflops, 4),
+        "roofline_frac_of_measured_mfma": round(achieved / mfma_tflops, 4),
+    }
+    out["roofline"]["traffic_source"] = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                                         "this command, scaled by the copy calibration; not measured in this run")
+
+    # ------------------------------------------------------------------ the other training workloads
+    if not args.no_other_configs:
+        del Q, Kt, V, dO, O, LSE, dQ, dK, dV
+        for key, owl in (("cfg3", wlm.CFG3), ("cfg4", wlm.CFG4)):
+            out[key] = train_leg(fa, wlm, owl, dev, max(3, K // 4), mfma_tflops)
+
     # ------------------------------------------------------------------ paged decode
     if not args.no_decode:
         dwl = wlm.CFG5
@@ -192,7 +276,9 @@ def main() -> int:
             "value": round(gbs, 1), "unit": "GB/s",
             "roofline": {"kernel": "decode_split+combine", "bound": "hbm", "achieved": round(gbs, 1),
                          "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
-                         "traffic": measured_traffic("decode_split")},
+                         "traffic": measured_traffic("decode_split"),
+                         "traffic_source": out["roofline"]["traffic_source"],
+                         "frac_of_measured_stream_read": round(gbs / read_gbs, 4)},
         }
         del Kp, Vp
 

@@ -345,6 +345,20 @@ int flexattn_paged_decode(const flexattn_decode_dims* dims,
                           float scale, void* O, float* LSE,
                           void* ws, size_t ws_bytes, void* stream);
 
+/* ---- measurement aids ------------------------------------------------------------------
+ * What the chip sustains for the two resources the hot path is bound by, from the simplest kernels
+ * that can reach them (bench.py times them with events and reports the library's kernels against
+ * these rates beside the datasheet peaks).  Asynchronous on `stream`, like every other call.
+ *   flexattn_probe_mfma         512 workgroups of 4 waves (two waves per SIMD) issue nothing but
+ *                               32x32x16 bf16 MFMAs on register operands, 16 * iters each;
+ *                               flexattn_probe_mfma_flops(iters) is the FLOP count of one launch.
+ *   flexattn_probe_stream_read  reads `bytes` bytes (device pointer, 16-byte aligned) once with
+ *                               16-byte loads.
+ * `sink` is a device float the kernels never really write (it keeps their work alive). */
+double flexattn_probe_mfma_flops(int64_t iters);
+int    flexattn_probe_mfma(int64_t iters, float* sink, void* stream);
+int    flexattn_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream);
+
 /* flexattn_paged_decode without a workspace argument, for callers that cannot allocate device
  * memory: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
  * partial results live in an array inside the library's device image (one copy per GPU, held until

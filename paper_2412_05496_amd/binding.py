@@ -145,6 +145,12 @@ def _lib():
                                           C.c_void_p, C.c_int64, C.c_void_p, C.c_uint32, C.c_uint32,
                                           P(_ModParams), C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+    lib.flexattn_probe_mfma_flops.restype = C.c_double
+    lib.flexattn_probe_mfma_flops.argtypes = [C.c_int64]
+    lib.flexattn_probe_mfma.restype = C.c_int
+    lib.flexattn_probe_mfma.argtypes = [C.c_int64, C.c_void_p, C.c_void_p]
+    lib.flexattn_probe_stream_read.restype = C.c_int
+    lib.flexattn_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.flexattn_paged_decode_static_capacity.restype = C.c_size_t
     lib.flexattn_paged_decode_static_capacity.argtypes = []
     lib.flexattn_paged_decode_static.restype = C.c_int
@@ -424,3 +430,16 @@ def flexattn_paged_decode_static(Q, K_pool, V_pool, page_table, ctx_lens, score_
                                                ctx_lens.data_ptr(), score_id, mask_id, C.byref(p), scale,
                                                O.data_ptr(), _ptr(LSE), _stream()), "flexattn_paged_decode_static")
     return O, LSE
+
+
+def flexattn_probe_mfma_flops(iters: int) -> float:
+    return _lib().flexattn_probe_mfma_flops(iters)
+
+
+def flexattn_probe_mfma(iters: int, sink: torch.Tensor):
+    _check(_lib().flexattn_probe_mfma(iters, sink.data_ptr(), _stream()), "flexattn_probe_mfma")
+
+
+def flexattn_probe_stream_read(src: torch.Tensor, sink: torch.Tensor):
+    _check(_lib().flexattn_probe_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                             _stream()), "flexattn_probe_stream_read")

@@ -32,7 +32,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.j
 
 def _units():
     units = [("blockmask", "blockmask.hip", []), ("fwd", "fwd.hip", []), ("bwd", "bwd.hip", []),
-             ("decode", "decode.hip", [])]
+             ("decode", "decode.hip", []), ("probe", "probe.hip", [])]
     for i in range(NUM_VARIANTS):
         units.append((f"fwd_inst_{i}", "fwd_inst.hip", [f"-DFLEXATTN_VARIANT={i}"]))
         units.append((f"bwd_inst_{i}", "bwd_inst.hip", [f"-DFLEXATTN_VARIANT={i}"]))
