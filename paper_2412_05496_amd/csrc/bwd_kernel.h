@@ -282,6 +282,10 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
                     });
                 }
                 read_rows(SLOT, 0, rcv4);
+                // relative bias: one value for the whole 32 x 32 block unless it lies near the diagonal
+                float rel_uni;
+                const bool rel_is_uni = smod.rel_uniform(q_off + q_first - (kv0 + 32 * kb + 31),
+                                                         q_off + q_first + 31 - (kv0 + 32 * kb), rel_uni);
                 u32x4 pk[2], dsk[2];
 #pragma unroll
                 for (int c4 = 0; c4 < 4; ++c4) {
@@ -301,7 +305,8 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
                         sv[i] = sacc[r];
                         rcv[i] = rcv4[r >> 2][r & 3];
                     }
-                    smod.p_with_grad4(sv, dqk, rcv, gr, pe);
+                    if (rel_is_uni) smod.template p_with_grad4<true>(sv, dqk, rcv, gr, pe, rel_uni);
+                    else smod.template p_with_grad4<false>(sv, dqk, rcv, gr, pe);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) ds[i] = pe[i] * gr[i] * dpacc[4 * c4 + i];
                     if (partial) {
@@ -540,12 +545,26 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
             // q_idx - kv_idx of element r is dq0 - 8 (r >> 2) - (r & 3)
             const int dq0 = q_pos - (kv0_cur + kvb * 32 + 4 * half);
             const float abase = smod.alibi_base(dq0);
+            float rel_uni;
+            const int kvs_blk = kv0_cur + kvb * 32;
+            const bool rel_is_uni = smod.rel_uniform(q_wave_min - (kvs_blk + 31), q_wave_min + 31 - kvs_blk, rel_uni);
+            auto rel = [&](int r) __attribute__((always_inline)) {
+                return typename decltype(smod)::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3)));
+            };
+            if (rel_is_uni) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float gr;
-                const float pe = smod.p_with_grad(sacc[r], typename decltype(smod)::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3))),
-                                                  rc, gr);
-                dpacc[r] = pe * gr * dpacc[r];
+                for (int r = 0; r < 16; ++r) {
+                    float gr;
+                    const float pe = smod.template p_with_grad<true>(sacc[r], rel(r), rc, gr, rel_uni);
+                    dpacc[r] = pe * gr * dpacc[r];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float gr;
+                    const float pe = smod.template p_with_grad<false>(sacc[r], rel(r), rc, gr);
+                    dpacc[r] = pe * gr * dpacc[r];
+                }
             }
             if (partial) {
                 asm volatile("" ::: "memory");   // keep this a branch

@@ -273,6 +273,7 @@ struct ScoreMod {
     float capl2;      // softcap * log2(e)
     const float* tab; // rel_bias row of head h
     int rel_max;
+    float rel_first, rel_last;   // first and last table entry, times k_tab
 
     __device__ __forceinline__ ScoreMod(const flexattn_mod_params& p, int h, float scale) {
         float mul = kCap ? (2.0f * kLog2e / p.softcap) : kLog2e;   // soft-cap needs exp(2 s / cap)
@@ -282,6 +283,27 @@ struct ScoreMod {
         tab = kRel ? p.rel_bias + (int64_t)h * p.rel_len : nullptr;
         rel_max = kRel ? p.rel_len - 1 : 0;
         capl2 = kCap ? p.softcap * kLog2e : 0.0f;
+        rel_first = kRel ? __builtin_bit_cast(float, ldc((const int32_t*)tab)) * k_tab : 0.0f;
+        rel_last = kRel ? __builtin_bit_cast(float, ldc((const int32_t*)tab + rel_max)) * k_tab : 0.0f;
+    }
+
+    // Relative bias of a whole block of scores whose q_idx - kv_idx spans [dq_min, dq_max]
+    // (wave-uniform bounds): the index is clamped to the table, so a block that lies at or beyond the
+    // last entry, or at or before the first, adds ONE value to all its scores -- almost every block
+    // of a long sequence -- and only the blocks near the diagonal look the table up per element.
+    // The functions below take UNI = true and that value (pre-multiplied like k_tab) for such blocks.
+    __device__ __forceinline__ bool rel_uniform(int dq_min, int dq_max, float& value) const {
+        value = 0.0f;
+        if constexpr (!kRel) return true;
+        if (dq_min >= rel_max) {
+            value = rel_last;
+            return true;
+        }
+        if (dq_max <= 0) {
+            value = rel_first;
+            return true;
+        }
+        return false;
     }
 
     // q_idx - kv_idx of one score element.  The kernels know it as dq0 + c with dq0 shared by the 16
@@ -297,10 +319,13 @@ struct ScoreMod {
     __device__ __forceinline__ float alibi_base(int dq0) const { return kAlibi ? k_bias * (float)dq0 : 0.0f; }
 
     // Scaled score plus the additive biases, times the factor the following exp2 needs.
-    __device__ __forceinline__ float pre(float acc, RelPos rp) const {
-        float y = acc * k_acc;
+    template <bool UNI = false>
+    __device__ __forceinline__ float pre(float acc, RelPos rp, float uni = 0.0f) const {
+        float y;
+        if constexpr (kRel && UNI) y = __builtin_fmaf(acc, k_acc, uni);
+        else y = acc * k_acc;
         if constexpr (kAlibi) y = __builtin_fmaf(k_bias, rp.c, y + rp.abase);
-        if constexpr (kRel) {
+        if constexpr (kRel && !UNI) {
             int r = rp.dq < 0 ? 0 : (rp.dq > rel_max ? rel_max : rp.dq);
             y = __builtin_fmaf(tab[r], k_tab, y);
         }
@@ -308,15 +333,17 @@ struct ScoreMod {
     }
 
     // Soft-cap only: r = 1 / (1 + exp(2 s / cap)), so that cap * tanh(s / cap) = cap * (1 - 2 r).
-    __device__ __forceinline__ float cap_r(float acc, RelPos dq) const {
-        return fast_rcp(1.0f + fast_exp2(pre(acc, dq)));
+    template <bool UNI = false>
+    __device__ __forceinline__ float cap_r(float acc, RelPos dq, float uni = 0.0f) const {
+        return fast_rcp(1.0f + fast_exp2(pre<UNI>(acc, dq, uni)));
     }
 
-    __device__ __forceinline__ float apply(float acc, RelPos dq) const {
+    template <bool UNI = false>
+    __device__ __forceinline__ float apply(float acc, RelPos dq, float uni = 0.0f) const {
         if constexpr (kCap) {
-            return __builtin_fmaf(-2.0f * capl2, cap_r(acc, dq), capl2);
+            return __builtin_fmaf(-2.0f * capl2, cap_r<UNI>(acc, dq, uni), capl2);
         } else {
-            return pre(acc, dq);
+            return pre<UNI>(acc, dq, uni);
         }
     }
 
@@ -336,11 +363,12 @@ struct ScoreMod {
     // The same for four independent elements, written stage by stage (pin4 keeps the stages apart):
     // a wave that is alone on its SIMD loses several cycles on every vector instruction that
     // consumes the result of the one before it.
+    template <bool UNI = false>
     __device__ __forceinline__ void p_with_grad4(const float (&acc)[4], const RelPos (&dq)[4], const float (&rc)[4],
-                                                 float (&g)[4], float (&p)[4]) const {
+                                                 float (&g)[4], float (&p)[4], float uni = 0.0f) const {
         float x[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = pre(acc[i], dq[i]);
+        for (int i = 0; i < 4; ++i) x[i] = pre<UNI>(acc[i], dq[i], uni);
         pin4(x);
         if constexpr (kCap) {
             float r[4];
@@ -370,14 +398,15 @@ struct ScoreMod {
         for (int i = 0; i < 4; ++i) p[i] = fast_exp2(x[i]);
         pin4(p);
     }
-    __device__ __forceinline__ float p_with_grad(float acc, RelPos dq, float rc, float& g) const {
+    template <bool UNI = false>
+    __device__ __forceinline__ float p_with_grad(float acc, RelPos dq, float rc, float& g, float uni = 0.0f) const {
         if constexpr (kCap) {
-            const float r = cap_r(acc, dq);
+            const float r = cap_r<UNI>(acc, dq, uni);
             g = __builtin_fmaf(-r, r, r);
             return fast_exp2(__builtin_fmaf(-2.0f * capl2, r, rc));
         } else {
             g = 1.0f;
-            return fast_exp2(pre(acc, dq) + rc);
+            return fast_exp2(pre<UNI>(acc, dq, uni) + rc);
         }
     }
 };

@@ -127,6 +127,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
 
     const ScoreMod<SCORE> smod(a.p, hq, a.scale);
     const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
+    const int q_wave_min = row * Bq + w * 32 + q_offset_of(a.p, b);   // the wave's rows: q_wave_min .. +31
     const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
     const float inv_neg2c = smod.capl2 > 0.0f ? -0.5f / smod.capl2 : 0.0f;   // 1 / (-2 cap log2 e)
 
@@ -194,13 +195,21 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
         auto rel = [&](int r) __attribute__((always_inline)) {
             return typename ScoreMod<SCORE>::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3)));
         };
+        // relative bias: one value for the whole block unless it lies near the diagonal
+        float rel_uni;
+        const bool rel_is_uni = smod.rel_uniform(q_wave_min - (kvs + 31), q_wave_min + 31 - kvs, rel_uni);
         if constexpr (BOUNDED) {
             // p = 2^(x - cap log2 e) = 2^(-2 cap log2 e * r), r = 1 / (1 + e): no maximum to track
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            auto prob = [&](float e) __attribute__((always_inline)) {
                 // -2 cap log2e / (1 + e) as ONE reciprocal: rcp((1 + e) / (-2 cap log2e))
-                const float e = fast_exp2(smod.pre(s[r], rel(r)));
-                s[r] = fast_exp2(fast_rcp(__builtin_fmaf(e, inv_neg2c, inv_neg2c)));
+                return fast_exp2(fast_rcp(__builtin_fmaf(e, inv_neg2c, inv_neg2c)));
+            };
+            if (rel_is_uni) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] = prob(fast_exp2(smod.template pre<true>(s[r], rel(r), rel_uni)));
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] = prob(fast_exp2(smod.template pre<false>(s[r], rel(r))));
             }
             if (partial) {
                 asm volatile("" ::: "memory");   // keep this a branch, not 16 selects on every tile
@@ -208,8 +217,13 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
                 for (int r = 0; r < 16; ++r) s[r] = keep(kvs + crow(r, half)) ? s[r] : 0.0f;
             }
         } else {
+            if (rel_is_uni) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = smod.apply(s[r], rel(r));
+                for (int r = 0; r < 16; ++r) s[r] = smod.template apply<true>(s[r], rel(r), rel_uni);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] = smod.template apply<false>(s[r], rel(r));
+            }
             if (partial) {
                 asm volatile("" ::: "memory");
 #pragma unroll
