@@ -224,18 +224,45 @@ def main() -> int:
     # ------------------------------------------------------------------ what the chip sustains
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
     probe_iters = 20000
-    fa.flexattn_probe_mfma(200, sink)
-    mfma_ms = event_time_ms(lambda: fa.flexattn_probe_mfma(probe_iters, sink), 3)
-    mfma_tflops = fa.flexattn_probe_mfma_flops(probe_iters) / (mfma_ms * 1e-3) / 1e12
+    clocks = torch.zeros(fa.flexattn_probe_mfma_waves(), 2, dtype=torch.int64, device=dev)
+
+    def mfma_probe(valu_mix: int, random_operands: bool):
+        """(TFLOP/s of the MFMAs, sustained core clock in GHz)"""
+        run = lambda n: fa.flexattn_probe_mfma(n, sink, valu_mix, random_operands, clocks)
+        run(2000)
+        ms = event_time_ms(lambda: run(probe_iters), 3)
+        ck = clocks.cpu().double()
+        return (fa.flexattn_probe_mfma_flops(probe_iters) / (ms * 1e-3) / 1e12,
+                float(ck[:, 0].sum() / (ck[:, 1].sum() * 10.0)))
+
+    mfma_const, ghz_const = mfma_probe(0, False)
+    mfma_tflops, ghz_random = mfma_probe(0, True)            # the rate every fraction below refers to
+    mix_const, _ = mfma_probe(1, False)
+    mix_random, ghz_mix = mfma_probe(1, True)
+    bwd_mix_random, ghz_bwd_mix = mfma_probe(2, True)
     stream_src = torch.empty(4 << 30, dtype=torch.uint8, device=dev).fill_(1)
     fa.flexattn_probe_stream_read(stream_src, sink)
     read_ms = event_time_ms(lambda: fa.flexattn_probe_stream_read(stream_src, sink), 5)
     read_gbs = stream_src.numel() / (read_ms * 1e-3) / 1e9
     del stream_src
     out["measured_peaks"] = {
-        "mfma_bf16_tflops": round(mfma_tflops, 1), "stream_read_gbs": round(read_gbs, 1),
-        "how": "flexattn_probe_mfma (32x32x16 bf16 MFMAs on register operands, 2 waves per SIMD) and "
-               "flexattn_probe_stream_read (4 GiB, 16-byte loads), events on the launch stream",
+        "mfma_bf16_tflops": round(mfma_tflops, 1), "mfma_core_ghz": round(ghz_random, 3),
+        "mfma_bf16_tflops_constant_operands": round(mfma_const, 1), "mfma_core_ghz_constant_operands": round(ghz_const, 3),
+        "mfma_with_softcap_valu_mix_tflops": round(mix_random, 1), "mfma_with_softcap_valu_mix_core_ghz": round(ghz_mix, 3),
+        "mfma_with_softcap_valu_mix_tflops_constant_operands": round(mix_const, 1),
+        "mfma_with_softcap_bwd_valu_mix_tflops": round(bwd_mix_random, 1),
+        "mfma_with_softcap_bwd_valu_mix_core_ghz": round(ghz_bwd_mix, 3),
+        # what the two stall-free instruction streams would give in credited FLOPs (the backward
+        # executes 7 GEMMs for the 5 it is credited with)
+        "fwd_frac_of_stall_free_mix": round(out["fwd_tflops"] / mix_random, 4),
+        "bwd_frac_of_stall_free_mix": round(out["bwd_tflops"] / (bwd_mix_random * 5 / 7), 4),
+        "stream_read_gbs": round(read_gbs, 1),
+        "how": "flexattn_probe_mfma: nothing but 32x32x16 bf16 MFMAs on register operands, 2 waves per SIMD, "
+               "operands of random sign / exponent / mantissa (the chip clocks lower the more the operands toggle: "
+               "compare the constant-operand figures); the valu_mix variant adds, independent of the MFMAs, the "
+               "vector instructions the soft-capped forward spends per MFMA, i.e. the hot loop's instruction mix "
+               "with nothing to wait for; flexattn_probe_stream_read: 4 GiB, 16-byte loads; events on the launch "
+               "stream, core clock from the waves' cycle and real-time counters",
         "fwd_frac_of_measured_mfma": round(out["fwd_tflops"] / mfma_tflops, 4),
         "bwd_frac_of_measured_mfma": round(out["bwd_tflops"] / mfma_tflops, 4),
         "roofline_frac_of_measured_mfma": round(achieved / mfma_tflops, 4),

@@ -349,15 +349,27 @@ int flexattn_paged_decode(const flexattn_decode_dims* dims,
  * What the chip sustains for the two resources the hot path is bound by, from the simplest kernels
  * that can reach them (bench.py times them with events and reports the library's kernels against
  * these rates beside the datasheet peaks).  Asynchronous on `stream`, like every other call.
- *   flexattn_probe_mfma         512 workgroups of 4 waves (two waves per SIMD) issue nothing but
- *                               32x32x16 bf16 MFMAs on register operands, 16 * iters each;
+ *   flexattn_probe_mfma         512 workgroups of 4 waves (two waves per SIMD) issue 16 * iters
+ *                               32x32x16 bf16 MFMAs each on register operands;
  *                               flexattn_probe_mfma_flops(iters) is the FLOP count of one launch.
+ *                               valu_mix = 1 puts behind every MFMA, independent of it, the vector
+ *                               instructions the soft-capped forward spends per MFMA (4 multiply-adds,
+ *                               3 transcendentals): the hot loop's instruction mix with nothing to
+ *                               wait for; valu_mix = 2 does the same for the soft-capped backward
+ *                               (3 multiply-adds, 2 transcendentals per MFMA of its two kernels).  random_operands != 0 feeds the MFMAs bf16 values of random
+ *                               sign, exponent and mantissa instead of small integers and ones: the
+ *                               chip's clock under load depends on how much the operands toggle.
+ *                               clocks: nullable device int64[2 * flexattn_probe_mfma_waves()]; wave w
+ *                               stores the core cycles and the 100 MHz ticks it spent in its loop
+ *                               (their ratio is the sustained core clock in units of 100 MHz).
  *   flexattn_probe_stream_read  reads `bytes` bytes (device pointer, 16-byte aligned) once with
  *                               16-byte loads.
  * `sink` is a device float the kernels never really write (it keeps their work alive). */
-double flexattn_probe_mfma_flops(int64_t iters);
-int    flexattn_probe_mfma(int64_t iters, float* sink, void* stream);
-int    flexattn_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream);
+double  flexattn_probe_mfma_flops(int64_t iters);
+int32_t flexattn_probe_mfma_waves(void);
+int     flexattn_probe_mfma(int64_t iters, int32_t valu_mix, int32_t random_operands, float* sink,
+                            int64_t* clocks, void* stream);
+int     flexattn_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream);
 
 /* flexattn_paged_decode without a workspace argument, for callers that cannot allocate device
  * memory: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The

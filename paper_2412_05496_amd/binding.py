@@ -148,7 +148,8 @@ def _lib():
     lib.flexattn_probe_mfma_flops.restype = C.c_double
     lib.flexattn_probe_mfma_flops.argtypes = [C.c_int64]
     lib.flexattn_probe_mfma.restype = C.c_int
-    lib.flexattn_probe_mfma.argtypes = [C.c_int64, C.c_void_p, C.c_void_p]
+    lib.flexattn_probe_mfma.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.flexattn_probe_mfma_waves.restype = C.c_int32
     lib.flexattn_probe_stream_read.restype = C.c_int
     lib.flexattn_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.flexattn_paged_decode_static_capacity.restype = C.c_size_t
@@ -436,8 +437,16 @@ def flexattn_probe_mfma_flops(iters: int) -> float:
     return _lib().flexattn_probe_mfma_flops(iters)
 
 
-def flexattn_probe_mfma(iters: int, sink: torch.Tensor):
-    _check(_lib().flexattn_probe_mfma(iters, sink.data_ptr(), _stream()), "flexattn_probe_mfma")
+def flexattn_probe_mfma_waves() -> int:
+    return _lib().flexattn_probe_mfma_waves()
+
+
+def flexattn_probe_mfma(iters: int, sink: torch.Tensor, valu_mix: int = 0, random_operands: bool = False,
+                        clocks: Optional[torch.Tensor] = None):
+    """clocks: optional int64 [flexattn_probe_mfma_waves(), 2] (core cycles, 100 MHz ticks) per wave."""
+    assert clocks is None or (clocks.dtype == torch.int64 and clocks.numel() >= 2 * flexattn_probe_mfma_waves())
+    _check(_lib().flexattn_probe_mfma(iters, valu_mix, int(random_operands), sink.data_ptr(), _ptr(clocks),
+                                      _stream()), "flexattn_probe_mfma")
 
 
 def flexattn_probe_stream_read(src: torch.Tensor, sink: torch.Tensor):

@@ -8,29 +8,96 @@ namespace flexattn {
 constexpr int kProbeBlocks = 512;          // two workgroups of four waves per CU: two waves per SIMD
 constexpr int kProbeUnroll = 16;
 
-// Nothing but v_mfma_f32_32x32x16_bf16 on register operands, four independent accumulators per wave.
-__global__ __launch_bounds__(256, 2) void probe_mfma_kernel(float* sink, long long iters) {
+// A counter-based hash -> a bf16 pair with magnitudes spread over [0.25, 4) and random signs: operands
+// that toggle the matrix pipe's inputs the way real activations do.
+__device__ __forceinline__ uint32_t probe_random_pair(uint32_t i) {
+    i *= 0x9E3779B1u;
+    i ^= i >> 15;
+    i *= 0x85EBCA77u;
+    i ^= i >> 13;
+    // per half: sign, exponent 125..128, seven mantissa bits
+    const uint32_t lo = (i & 0x8000u) | ((125u + ((i >> 7) & 3u)) << 7) | (i & 0x7fu);
+    const uint32_t hi = ((i >> 16) & 0x8000u) | ((125u + ((i >> 23) & 3u)) << 7) | ((i >> 16) & 0x7fu);
+    return lo | (hi << 16);
+}
+
+// VALU_MIX = 0: nothing but v_mfma_f32_32x32x16_bf16 on register operands, four independent
+// accumulators per wave.  VALU_MIX = 1: behind every MFMA, independent of it, the vector work the
+// soft-capped forward does per MFMA (3 multiply-adds and 3 transcendentals, plus the pack and row
+// sum as one more multiply-add): the instruction mix of the hot loop with every operand in
+// registers -- no LDS, no global memory, no barrier, no dependence to wait for.  VALU_MIX = 2: the
+// same for the soft-capped backward (its two MFMA kernels together spend 3 multiply-adds and 2
+// transcendentals per MFMA).
+// RANDOM: operands from probe_random_pair instead of small integers and ones.
+// clocks[2 * wave], clocks[2 * wave + 1]: core cycles and 100 MHz ticks the wave spent in the loop.
+template <int VALU_MIX, bool RANDOM>
+__global__ __launch_bounds__(256, 2) void probe_mfma_kernel(float* sink, long long* clocks, long long iters) {
     f32x16 acc[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
-    bf16x8 x, y;
+    bf16x8 x[4], y[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        x[i] = (bf16)(float)((threadIdx.x + i) & 3);
-        y[i] = (bf16)1.0f;
+    for (int j = 0; j < 4; ++j) {
+        u32x4 xa, ya;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t n = (threadIdx.x * 4 + j) * 8 + i;
+            xa[i] = RANDOM ? probe_random_pair(2 * n) : (0x3f800000u | (((n & 1) ? 0x3f80u : 0x4000u)));
+            ya[i] = RANDOM ? probe_random_pair(2 * n + 1) : 0x3f803f80u;
+        }
+        x[j] = __builtin_bit_cast(bf16x8, xa);
+        y[j] = __builtin_bit_cast(bf16x8, ya);
     }
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = 0.001f * (float)(threadIdx.x + i);
+    const float c0 = 0.99f, c1 = 0.01f;
+    const long long t0 = __builtin_readcyclecounter(), r0 = wall_clock64();
     for (long long it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int u = 0; u < kProbeUnroll; ++u) acc[u & 3] = mfma32(x, y, acc[u & 3]);
+        for (int u = 0; u < kProbeUnroll; ++u) {
+            acc[u & 3] = mfma32(x[u & 3], y[(u >> 2) & 3], acc[u & 3]);
+            if constexpr (VALU_MIX == 2) {
+                float& a = v[(2 * u) & 7];
+                float& b = v[(2 * u + 1) & 7];
+                asm volatile("v_fma_f32 %0, %0, %2, %3\n\tv_exp_f32 %1, %1\n\tv_fma_f32 %0, %0, %2, %3\n\t"
+                             "v_rcp_f32 %1, %1\n\tv_fma_f32 %0, %0, %2, %3"
+                             : "+v"(a), "+v"(b) : "v"(c0), "v"(c1));
+            }
+            if constexpr (VALU_MIX == 1) {
+                float& a = v[(2 * u) & 7];
+                float& b = v[(2 * u + 1) & 7];
+                // (asm: the compiler must neither fold nor regroup these)
+                asm volatile("v_fma_f32 %0, %0, %2, %3\n\tv_exp_f32 %1, %1\n\tv_fma_f32 %0, %0, %2, %3\n\t"
+                             "v_rcp_f32 %1, %1\n\tv_fma_f32 %0, %0, %2, %3\n\tv_exp_f32 %1, %1\n\t"
+                             "v_fma_f32 %1, %1, %2, %3"
+                             : "+v"(a), "+v"(b) : "v"(c0), "v"(c1));
+            }
+        }
+        // fold the accumulators back now and then so that random operands never reach infinity
+        if ((it & 255) == 255) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][r] *= 9.5367431640625e-07f;
+        }
     }
+    const long long t1 = __builtin_readcyclecounter(), r1 = wall_clock64();
     float s = 0.0f;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s += acc[j][r];
-    if (s == -1.0f) sink[0] = s;            // never true: keeps the accumulators alive
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += v[i];
+    if (s == -1.2345f) sink[0] = s;         // practically never true: keeps the work alive
+    if (clocks && (threadIdx.x & 63) == 0) {
+        const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+        clocks[2 * wave] = t1 - t0;
+        clocks[2 * wave + 1] = r1 - r0;
+    }
 }
 
 // Grid-stride read of 16 bytes per lane, four loads in flight per lane; the sum keeps the loads alive.
@@ -59,9 +126,20 @@ extern "C" double flexattn_probe_mfma_flops(int64_t iters) {
     return (double)kProbeBlocks * 4.0 * (double)iters * kProbeUnroll * 32768.0;
 }
 
-extern "C" int flexattn_probe_mfma(int64_t iters, float* sink, void* stream) {
-    if (!sink || iters <= 0) return FLEXATTN_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(probe_mfma_kernel, dim3(kProbeBlocks), dim3(256), 0, (hipStream_t)stream, sink, (long long)iters);
+extern "C" int32_t flexattn_probe_mfma_waves(void) { return kProbeBlocks * 4; }
+
+extern "C" int flexattn_probe_mfma(int64_t iters, int32_t valu_mix, int32_t random_operands, float* sink,
+                                   int64_t* clocks, void* stream) {
+    if (!sink || iters <= 0 || valu_mix < 0 || valu_mix > 2) return FLEXATTN_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    long long* ck = (long long*)clocks;
+    const dim3 grid(kProbeBlocks), block(256);
+    if (valu_mix == 0 && !random_operands) hipLaunchKernelGGL((probe_mfma_kernel<0, false>), grid, block, 0, st, sink, ck, (long long)iters);
+    if (valu_mix == 0 && random_operands) hipLaunchKernelGGL((probe_mfma_kernel<0, true>), grid, block, 0, st, sink, ck, (long long)iters);
+    if (valu_mix == 1 && !random_operands) hipLaunchKernelGGL((probe_mfma_kernel<1, false>), grid, block, 0, st, sink, ck, (long long)iters);
+    if (valu_mix == 1 && random_operands) hipLaunchKernelGGL((probe_mfma_kernel<1, true>), grid, block, 0, st, sink, ck, (long long)iters);
+    if (valu_mix == 2 && !random_operands) hipLaunchKernelGGL((probe_mfma_kernel<2, false>), grid, block, 0, st, sink, ck, (long long)iters);
+    if (valu_mix == 2 && random_operands) hipLaunchKernelGGL((probe_mfma_kernel<2, true>), grid, block, 0, st, sink, ck, (long long)iters);
     FLEXATTN_HIP_TRY(hipGetLastError());
     return FLEXATTN_OK;
 }
