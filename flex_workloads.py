@@ -234,4 +234,7 @@ def blockmask_all_partial(alloc_blockmask, bm):
         ofidx.zero_()
     if bm.stats is not None and out.stats is not None:
         out.stats.copy_(bm.stats)
+    for name in ("kv_order", "q_order"):      # listed blocks per line are unchanged, so is the work order
+        if getattr(bm, name, None) is not None and getattr(out, name, None) is not None:
+            getattr(out, name).copy_(getattr(bm, name))
     return out

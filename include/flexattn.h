@@ -146,6 +146,17 @@ typedef struct flexattn_tensor {
  *
  * Bm is 1 (the mask ignores b) or the batch size; Hm is 1 or the number of QUERY heads.
  * All arrays are int32, dense, row-major.
+ *
+ * Work order (nullable, optional; not in the paper): the workgroups of a launch start in index
+ * order and a launch ends with its slowest workgroup, so for masks whose rows differ in length
+ * (documents, sliding windows with a prefix, ...) the kernels take the rows of blocks longest first:
+ *   kv_order [Bm, Hm, NR]  the rows of blocks sorted by descending number of listed blocks
+ *                          (kv_num_blocks + full_kv_num_blocks), ties by ascending index
+ *   q_order  [Bm, Hm, NC]  the same for the columns of blocks (q_num_blocks + full_q_num_blocks)
+ * A line count above 8192 is not sorted: kv_order is then NR-1, ..., 0 and q_order 0, ..., NC-1
+ * (the best fixed orders for causal-like masks).  flexattn_blockmask_build fills the arrays that
+ * are non-NULL; forward / backward use them when present and those fixed orders otherwise.  The
+ * order changes which workgroup computes which block of rows, never a result.
  */
 typedef struct flexattn_blockmask {
     int32_t  Bm, Hm, q_len, kv_len, Bq, Bk;
@@ -157,17 +168,21 @@ typedef struct flexattn_blockmask {
     int32_t* q_indices;
     int32_t* full_q_num_blocks;
     int32_t* full_q_indices;
+    int32_t* kv_order;      /* nullable */
+    int32_t* q_order;       /* nullable */
 } flexattn_blockmask;
 
 /* Geometry and element counts of the eight arrays of a BlockMask (section 4.2), so that a caller
  * can allocate them without repeating the library's rounding: NR = ceil(q_len / Bq),
- * NC = ceil(kv_len / Bk); counts are in int32 elements, in the order of flexattn_blockmask.
+ * NC = ceil(kv_len / Bk); counts are in int32 elements, in the order of flexattn_blockmask
+ * (the eight lists, then the two optional order arrays).
  * Host-only arithmetic.  FLEXATTN_ERR_INVALID_ARG for a non-positive argument or a NULL `sizes`,
  * FLEXATTN_ERR_UNSUPPORTED if Bm * Hm * NR * NC exceeds 2^31 (the limit of flexattn_blockmask_build). */
 typedef struct flexattn_blockmask_counts {
     int32_t NR, NC;
     int64_t kv_num_blocks, kv_indices, full_kv_num_blocks, full_kv_indices;
     int64_t q_num_blocks, q_indices, full_q_num_blocks, full_q_indices;
+    int64_t kv_order, q_order;
 } flexattn_blockmask_counts;
 int flexattn_blockmask_sizes(int32_t Bm, int32_t Hm, int32_t q_len, int32_t kv_len, int32_t Bq, int32_t Bk,
                                 flexattn_blockmask_counts* sizes);

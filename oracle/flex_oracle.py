@@ -410,7 +410,24 @@ def create_block_mask(mask_mod: MaskMod, Bm: int, Hm: int, q_len: int, kv_len: i
     out["full_q_num_blocks"], out["full_q_indices"] = _compact(full.transpose(-1, -2))
     out["stats"] = {"partial": int(partial.sum()), "full": int(full.sum()),
                     "total": kinds.numel(), "unmasked_pairs": pairs}
+    out["kv_order"] = work_order(out["kv_num_blocks"] + out["full_kv_num_blocks"], reversed_when_long=True)
+    out["q_order"] = work_order(out["q_num_blocks"] + out["full_q_num_blocks"], reversed_when_long=False)
     return out
+
+
+WORK_ORDER_MAX_LINES = 8192
+
+
+def work_order(counts: torch.Tensor, reversed_when_long: bool) -> torch.Tensor:
+    """Not in the paper: the order in which a launch should take the rows (columns) of blocks so that
+    its longest ones start first -- the lines of each plane by descending number of listed blocks,
+    ties by ascending index.  counts [Bm, Hm, n] -> int32 [Bm, Hm, n], a permutation per plane.
+    More than WORK_ORDER_MAX_LINES lines are not sorted: n-1 .. 0 (rows) resp. 0 .. n-1 (columns)."""
+    n = counts.shape[-1]
+    if n > WORK_ORDER_MAX_LINES:
+        line = torch.arange(n - 1, -1, -1) if reversed_when_long else torch.arange(n)
+        return line.expand(counts.shape).to(torch.int32).contiguous()
+    return torch.argsort(counts.to(torch.int64), dim=-1, descending=True, stable=True).to(torch.int32)
 
 
 def convert_block_mask_paged(num_blocks: torch.Tensor, indices: torch.Tensor, page_table: torch.Tensor,

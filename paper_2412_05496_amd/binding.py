@@ -68,13 +68,14 @@ class _BlockMask(C.Structure):
                 ("kv_num_blocks", C.c_void_p), ("kv_indices", C.c_void_p),
                 ("full_kv_num_blocks", C.c_void_p), ("full_kv_indices", C.c_void_p),
                 ("q_num_blocks", C.c_void_p), ("q_indices", C.c_void_p),
-                ("full_q_num_blocks", C.c_void_p), ("full_q_indices", C.c_void_p)]
+                ("full_q_num_blocks", C.c_void_p), ("full_q_indices", C.c_void_p),
+                ("kv_order", C.c_void_p), ("q_order", C.c_void_p)]
 
 
 class _BlockMaskSizes(C.Structure):
     _fields_ = [("NR", C.c_int32), ("NC", C.c_int32)] + [(n, C.c_int64) for n in (
         "kv_num_blocks", "kv_indices", "full_kv_num_blocks", "full_kv_indices",
-        "q_num_blocks", "q_indices", "full_q_num_blocks", "full_q_indices")]
+        "q_num_blocks", "q_indices", "full_q_num_blocks", "full_q_indices", "kv_order", "q_order")]
 
 
 class _Dims(C.Structure):
@@ -237,13 +238,16 @@ class BlockMask:
     full_q_num_blocks: torch.Tensor
     full_q_indices: torch.Tensor
     stats: Optional[torch.Tensor] = None     # int64[4]: partial, full, total blocks, unmasked scalars
+    kv_order: Optional[torch.Tensor] = None  # [Bm, Hm, NR] rows of blocks, longest first (optional)
+    q_order: Optional[torch.Tensor] = None   # [Bm, Hm, NC] columns of blocks, longest first (optional)
 
     def _c(self) -> _BlockMask:
         return _BlockMask(self.Bm, self.Hm, self.q_len, self.kv_len, self.Bq, self.Bk,
                           self.kv_num_blocks.data_ptr(), self.kv_indices.data_ptr(),
                           self.full_kv_num_blocks.data_ptr(), self.full_kv_indices.data_ptr(),
                           self.q_num_blocks.data_ptr(), self.q_indices.data_ptr(),
-                          self.full_q_num_blocks.data_ptr(), self.full_q_indices.data_ptr())
+                          self.full_q_num_blocks.data_ptr(), self.full_q_indices.data_ptr(),
+                          _ptr(self.kv_order), _ptr(self.q_order))
 
 
 def _tensor(t: torch.Tensor) -> _Tensor:
@@ -262,9 +266,11 @@ def flexattn_blockmask_sizes(Bm: int, Hm: int, q_len: int, kv_len: int, Bq: int,
     return sizes
 
 
-def alloc_blockmask(Bm: int, Hm: int, q_len: int, kv_len: int, Bq: int, Bk: int, device="cuda") -> BlockMask:
-    """Caller-side allocation of the eight int32 arrays (the library allocates nothing), sized by
-    flexattn_blockmask_sizes and viewed as [Bm, Hm, NR(, NC)] / [Bm, Hm, NC(, NR)]."""
+def alloc_blockmask(Bm: int, Hm: int, q_len: int, kv_len: int, Bq: int, Bk: int, device="cuda",
+                    work_order: bool = True) -> BlockMask:
+    """Caller-side allocation of the eight int32 arrays and (work_order) the two order arrays (the
+    library allocates nothing), sized by flexattn_blockmask_sizes and viewed as
+    [Bm, Hm, NR(, NC)] / [Bm, Hm, NC(, NR)]."""
     sz = flexattn_blockmask_sizes(Bm, Hm, q_len, kv_len, Bq, Bk)
     i32 = dict(dtype=torch.int32, device=device)
 
@@ -276,7 +282,9 @@ def alloc_blockmask(Bm: int, Hm: int, q_len: int, kv_len: int, Bq: int, Bk: int,
                      arr(sz.full_kv_num_blocks, sz.NR), arr(sz.full_kv_indices, sz.NR, sz.NC),
                      arr(sz.q_num_blocks, sz.NC), arr(sz.q_indices, sz.NC, sz.NR),
                      arr(sz.full_q_num_blocks, sz.NC), arr(sz.full_q_indices, sz.NC, sz.NR),
-                     torch.empty(4, dtype=torch.int64, device=device))
+                     torch.empty(4, dtype=torch.int64, device=device),
+                     arr(sz.kv_order, sz.NR) if work_order else None,
+                     arr(sz.q_order, sz.NC) if work_order else None)
 
 
 def flexattn_is_supported(mask_id: int, score_id: int, D: int) -> bool:

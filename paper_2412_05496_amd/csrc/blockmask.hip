@@ -99,6 +99,49 @@ __global__ __launch_bounds__(64) void compact_lines_kernel(
     }
 }
 
+// Work order of one orientation: per plane, the lines sorted by descending num_a + num_b (ties by
+// ascending index) with a bitonic sort of (kOrderCountMax - count, index) keys in LDS; more than
+// kOrderMax lines are left in the fixed order (descending index if `reversed`, else ascending).
+constexpr int kOrderMax = 8192, kOrderIdxBits = 13, kOrderCountMax = (1 << 18) - 1;
+__global__ __launch_bounds__(256) void order_lines_kernel(const int32_t* __restrict__ num_a,
+                                                          const int32_t* __restrict__ num_b, int n, int reversed,
+                                                          int32_t* __restrict__ order) {
+    __shared__ uint32_t keys[kOrderMax];
+    const int64_t base = (int64_t)blockIdx.x * n;
+    if (n > kOrderMax) {
+        for (int i = threadIdx.x; i < n; i += 256) order[base + i] = reversed ? n - 1 - i : i;
+        return;
+    }
+    int n_pad = 1;
+    while (n_pad < n) n_pad <<= 1;
+    for (int i = threadIdx.x; i < n_pad; i += 256) {
+        uint32_t key = 0xffffffffu;
+        if (i < n) {
+            const int cnt = min(num_a[base + i] + num_b[base + i], kOrderCountMax);
+            key = ((uint32_t)(kOrderCountMax - cnt) << kOrderIdxBits) | (uint32_t)i;
+        }
+        keys[i] = key;
+    }
+    __syncthreads();
+    for (int k = 2; k <= n_pad; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = threadIdx.x; i < n_pad; i += 256) {
+                const int partner = i ^ j;
+                if (partner > i) {
+                    const uint32_t x = keys[i], y = keys[partner];
+                    const bool ascending = (i & k) == 0;
+                    if ((x > y) == ascending) {
+                        keys[i] = y;
+                        keys[partner] = x;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int i = threadIdx.x; i < n; i += 256) order[base + i] = (int32_t)(keys[i] & ((1u << kOrderIdxBits) - 1));
+}
+
 __global__ void zero_stats_kernel(unsigned long long* stats) {
     if (threadIdx.x < 4) stats[threadIdx.x] = 0;
 }
@@ -149,6 +192,8 @@ extern "C" int flexattn_blockmask_sizes(int32_t Bm, int32_t Hm, int32_t q_len, i
     sizes->kv_indices = sizes->full_kv_indices = planes * NR * NC;
     sizes->q_num_blocks = sizes->full_q_num_blocks = planes * NC;
     sizes->q_indices = sizes->full_q_indices = planes * NC * NR;
+    sizes->kv_order = planes * NR;
+    sizes->q_order = planes * NC;
     return FLEXATTN_OK;
 }
 
@@ -213,6 +258,12 @@ extern "C" int flexattn_blockmask_build(uint32_t mask_id, const flexattn_mod_par
     hipLaunchKernelGGL(compact_lines_kernel, dim3((unsigned)(planes * NC)), dim3(64), 0, st, kinds, NC, NR,
                        (long long)NR * NC, 1ll, (long long)NC, bm->q_num_blocks, bm->q_indices,
                        bm->full_q_num_blocks, bm->full_q_indices);
+    if (bm->kv_order)
+        hipLaunchKernelGGL(order_lines_kernel, dim3((unsigned)planes), dim3(256), 0, st, bm->kv_num_blocks,
+                           bm->full_kv_num_blocks, NR, 1, bm->kv_order);
+    if (bm->q_order)
+        hipLaunchKernelGGL(order_lines_kernel, dim3((unsigned)planes), dim3(256), 0, st, bm->q_num_blocks,
+                           bm->full_q_num_blocks, NC, 0, bm->q_order);
     FLEXATTN_HIP_TRY(hipGetLastError());
     return FLEXATTN_OK;
 }

@@ -80,6 +80,7 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
     a.full_kv_num = bm->full_kv_num_blocks; a.full_kv_idx = bm->full_kv_indices;
     a.q_num = bm->q_num_blocks; a.q_idx = bm->q_indices;
     a.full_q_num = bm->full_q_num_blocks; a.full_q_idx = bm->full_q_indices;
+    a.kv_order = bm->kv_order; a.q_order = bm->q_order;
     a.scale = scale;
     if (params) a.p = *params;
 

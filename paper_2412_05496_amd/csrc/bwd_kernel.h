@@ -53,6 +53,8 @@ struct BwdArgs {
     const int32_t* q_idx;
     const int32_t* full_q_num;
     const int32_t* full_q_idx;
+    const int32_t* kv_order;   // nullable work orders (rows / columns of blocks, longest first)
+    const int32_t* q_order;
     float scale;
     flexattn_mod_params p;
 };
@@ -113,19 +115,30 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
     __shared__ __attribute__((aligned(1024))) bf16 smem[2 * 2 * TILE];        // 2 x (Q tile, dO tile)
     __shared__ __attribute__((aligned(1024))) u32x4 s_xchg[4][2][64];         // [wave][16-row slice][lane]
     __shared__ __attribute__((aligned(256))) float s_row[2][2][TQ];           // [slot][rc | -delta][row]
-    constexpr int kListMax = 1024;
+    constexpr int kListMax = 512;
     __shared__ int s_steps[kListMax + 2];          // the walk of the current head, see below
+    using Score = ScoreMod<SCORE, true>;
+    __shared__ float s_rel[Score::kRel ? kRelTableMax : 1];   // relative-bias row of the current head
 
-    // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD
+    // workgroup -> (b, hkv, 64-key tile); all tiles of one (b, hkv) on one XCD.  The columns of
+    // blocks are taken in the BlockMask's work order (longest first; that of the group's first query
+    // head where the mask has a plane per head), the 64-key tiles of a column side by side.
     const int units = a.B * a.Hkv;
-    const int tiles = (a.kv_len + 63) / 64;
+    const int sub_k = a.Bk / 64;                   // tiles per column of blocks
+    const int slots = a.NC * sub_k;                // >= tiles: the last column may be cut short
     const int id = blockIdx.x, xcd = id & 7, kk = id >> 3;
-    const int unit = (kk / tiles) * 8 + xcd;
+    const int unit = (kk / slots) * 8 + xcd;
     if (unit >= units) return;
-    const int tile = kk % tiles;
     const int b = unit / a.Hkv, hkv = unit % a.Hkv;
+    const int slot = kk % slots;
+    int col = slot / sub_k;
+    if (a.q_order) {
+        const int64_t plane0 = (int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hkv * a.G : 0);
+        col = a.q_order[plane0 * a.NC + col];
+    }
+    const int tile = col * sub_k + slot % sub_k;
     const int kv0 = tile * 64;
-    const int col = kv0 / a.Bk;         // column of BlockMask blocks this tile lies in
+    if (kv0 >= a.kv_len) return;
 
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -183,7 +196,10 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
         // waves 0, 2 fetch the rc row, waves 1, 3 the -delta row (the duplicates write the same values)
         const i32x4 row_rsrc =
             make_rsrc(((w & 1) ? a.delta : a.lse2) + ((int64_t)b * a.Hq + hq) * a.q_len, (uint32_t)a.q_len * 4u);
-        const ScoreMod<SCORE> smod(a.p, hq, a.scale);
+        const Score smod(a.p, hq, a.scale, lds_addr(s_rel));
+        // (the previous head's last step ended with a barrier: nobody reads its row any more; the
+        // barrier behind the first segment's walk makes this one visible)
+        smod.fill_table(tid, 256);
 
         // The merged list (FULL blocks, then PARTIAL ones) is walked from its END: every workgroup of
         // a head then spends most of its time descending from the last row block, so the workgroups
@@ -292,7 +308,7 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
                     float sv[4], rcv[4], gr[4], pe[4], ds[4];
                     // alibi / rel-bias need q - kv = dq0 + 8 (r >> 2) + (r & 3); the soft-cap and the plain score do not
                     using RelPos = typename decltype(smod)::RelPos;
-                    constexpr bool kNeedsPos = ScoreMod<SCORE>::kAlibi || ScoreMod<SCORE>::kRel;
+                    constexpr bool kNeedsPos = Score::kAlibi || Score::kRel;
                     const int dq0 = kNeedsPos ? q_off + q_first + 4 * half - kv_lane : 0;
                     const float abase = smod.alibi_base(dq0);
                     auto rel = [&](int r) __attribute__((always_inline)) {
@@ -403,6 +419,7 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
     __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];   // K(even), K(odd), V(even), V(odd)
     constexpr int kTabAlibi = 1024;                                  // the table has at most 1024 entries
     __shared__ float s_tab[CAPTURED ? kTabAlibi + 1 : 1];            // relative-bias entries, then the ALiBi sum
+    __shared__ float s_rel[ScoreMod<SCORE>::kRel ? kRelTableMax : 1]; // relative-bias row of the head (values)
 
     const int units = a.B * a.Hkv;
     const int id = blockIdx.x, xcd = id & 7, kk = id >> 3;
@@ -410,9 +427,10 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
     const int unit = (kk / per_unit) * 8 + xcd;
     if (unit >= units) return;
     const int rem = kk % per_unit;
-    const int row = a.NR - 1 - rem / a.G;
     const int g = rem % a.G;
     const int b = unit / a.Hkv, hkv = unit % a.Hkv, hq = hkv * a.G + g;
+    const int64_t plane = (int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hq : 0);
+    const int row = a.kv_order ? ldc(a.kv_order + plane * a.NR + rem / a.G) : a.NR - 1 - rem / a.G;
 
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -457,7 +475,8 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
     const i32x4 k_rsrc = make_rsrc(a.K + b * a.k_sb + hkv * a.k_sh, (uint32_t)((a.kv_len - 1) * a.k_ss + D) * 2u);
     const i32x4 v_rsrc = make_rsrc(a.V + b * a.v_sb + hkv * a.v_sh, (uint32_t)((a.kv_len - 1) * a.v_ss + D) * 2u);
     const int k_row_bytes = (int)a.k_ss * 2, v_row_bytes = (int)a.v_ss * 2;
-    const ScoreMod<SCORE> smod(a.p, hq, a.scale);
+    const ScoreMod<SCORE, true> smod(a.p, hq, a.scale, lds_addr(s_rel));
+    smod.fill_table(tid, NW * 64);                  // visible after the prologue's barrier
     const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
     const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
 
@@ -674,7 +693,7 @@ constexpr uint32_t kBwdStageCaptured = 8u;   // internal: the captured-tensor su
 template <uint32_t MASK, uint32_t SCORE>
 int launch_bwd_variant(const BwdArgs& a, int D, uint32_t stages, hipStream_t st) {
     const int units = a.B * a.Hkv;
-    const unsigned grid_kv = (unsigned)(((units + 7) / 8) * 8 * ((a.kv_len + 63) / 64));
+    const unsigned grid_kv = (unsigned)(((units + 7) / 8) * 8 * (a.NC * (a.Bk / 64)));
     const unsigned grid_q = (unsigned)(((units + 7) / 8) * 8 * a.G * a.NR);
     const bool kv = stages & FLEXATTN_BWD_DKDV, q = stages & FLEXATTN_BWD_DQ;
     if (stages & FLEXATTN_BWD_DELTA) {

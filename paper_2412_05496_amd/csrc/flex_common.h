@@ -262,7 +262,12 @@ __device__ __forceinline__ void pin4(float (&v)[4]) {
     asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
 }
 
-template <uint32_t SCORE>
+// LDSTAB: the relative-bias row of the head has been copied to LDS (fill_table), pre-multiplied, and
+// is looked up there: one 32-bit address per score instead of a 64-bit global address, which is
+// what keeps the table variant of the MFMA kernels inside their register budget.
+constexpr int kRelTableMax = 1024;         // flexattn_mod_params::rel_len is at most this
+
+template <uint32_t SCORE, bool LDSTAB = false>
 struct ScoreMod {
     static constexpr bool kAlibi = SCORE & FLEXATTN_SCORE_ALIBI;
     static constexpr bool kRel = SCORE & FLEXATTN_SCORE_REL_BIAS;
@@ -274,8 +279,10 @@ struct ScoreMod {
     const float* tab; // rel_bias row of head h
     int rel_max;
     float rel_first, rel_last;   // first and last table entry, times k_tab
+    uint32_t tab_lds; // LDSTAB: LDS byte address of the pre-multiplied row
 
-    __device__ __forceinline__ ScoreMod(const flexattn_mod_params& p, int h, float scale) {
+    __device__ __forceinline__ ScoreMod(const flexattn_mod_params& p, int h, float scale, uint32_t tab_lds_ = 0)
+        : tab_lds(tab_lds_) {
         float mul = kCap ? (2.0f * kLog2e / p.softcap) : kLog2e;   // soft-cap needs exp(2 s / cap)
         k_acc = scale * mul;
         k_bias = kAlibi ? p.alibi_bias[h] * mul : 0.0f;
@@ -285,6 +292,15 @@ struct ScoreMod {
         capl2 = kCap ? p.softcap * kLog2e : 0.0f;
         rel_first = kRel ? __builtin_bit_cast(float, ldc((const int32_t*)tab)) * k_tab : 0.0f;
         rel_last = kRel ? __builtin_bit_cast(float, ldc((const int32_t*)tab + rel_max)) * k_tab : 0.0f;
+    }
+
+    // LDSTAB: every thread of the workgroup copies its share of the head's row (a barrier must follow
+    // before the first lookup, and precede the next fill)
+    __device__ __forceinline__ void fill_table(int tid, int nthreads) const {
+        if constexpr (kRel && LDSTAB) {
+            for (int i = tid; i <= rel_max; i += nthreads)
+                *(__attribute__((address_space(3))) float*)(uintptr_t)(tab_lds + 4u * (uint32_t)i) = tab[i] * k_tab;
+        }
     }
 
     // Relative bias of a whole block of scores whose q_idx - kv_idx spans [dq_min, dq_max]
@@ -327,7 +343,8 @@ struct ScoreMod {
         if constexpr (kAlibi) y = __builtin_fmaf(k_bias, rp.c, y + rp.abase);
         if constexpr (kRel && !UNI) {
             int r = rp.dq < 0 ? 0 : (rp.dq > rel_max ? rel_max : rp.dq);
-            y = __builtin_fmaf(tab[r], k_tab, y);
+            if constexpr (LDSTAB) y += *(const __attribute__((address_space(3))) float*)(uintptr_t)(tab_lds + 4u * (uint32_t)r);
+            else y = __builtin_fmaf(tab[r], k_tab, y);
         }
         return y;
     }

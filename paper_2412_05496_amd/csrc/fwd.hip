@@ -98,6 +98,7 @@ extern "C" int flexattn_forward(const flexattn_dims* dims, const flexattn_tensor
     a.bm_Bm = bm->Bm; a.bm_Hm = bm->Hm;
     a.kv_num = bm->kv_num_blocks; a.kv_idx = bm->kv_indices;
     a.full_num = bm->full_kv_num_blocks; a.full_idx = bm->full_kv_indices;
+    a.kv_order = bm->kv_order;
     a.scale = scale;
     if (params) a.p = *params;
     rc = kFwdLaunchers[vi](a, dims->D, bm->Bq, (hipStream_t)stream);
@@ -139,6 +140,7 @@ extern "C" int flexattn_paged_forward(const flexattn_dims* dims, const flexattn_
     a.bm_Bm = bm->Bm; a.bm_Hm = bm->Hm;
     a.kv_num = bm->kv_num_blocks; a.kv_idx = bm->kv_indices;
     a.full_num = bm->full_kv_num_blocks; a.full_idx = bm->full_kv_indices;
+    a.kv_order = bm->kv_order;
     a.phys_kv_idx = phys_kv_indices; a.phys_full_idx = phys_full_kv_indices;
     a.page_stride = (int64_t)dims->Hkv * page_size * dims->D;
     a.n_pool_pages = n_pool_pages;

@@ -37,6 +37,7 @@ struct FwdArgs {
     const int32_t* kv_idx;
     const int32_t* full_num;
     const int32_t* full_idx;
+    const int32_t* kv_order;   // nullable: rows of blocks, longest first
     float scale;
     flexattn_mod_params p;
     // paged K/V (section 5.1): K, V point at the pools, k_sb = v_sb = 0, k_sh = v_sh = page_size * D,
@@ -60,10 +61,13 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
     constexpr int TILE = kTileKV * D;              // elements per LDS tile
 
     __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];   // K(even), K(odd), V(even), V(odd)
+    using Score = ScoreMod<SCORE, true>;
+    __shared__ float s_rel[Score::kRel ? kRelTableMax : 1];           // relative-bias row of the head
 
     // ---- workgroup -> (b, hkv, g, row of blocks).  Consecutive workgroup ids go to the 8 XCDs in
     // turn; all rows and all G query heads of one (b, hkv) are sent to the same XCD so that its K/V
-    // stay in that XCD's L2.  Rows are taken last-first (causal-like masks: longest first).
+    // stay in that XCD's L2.  Rows are taken longest first (the BlockMask's work order), or
+    // last-first without one (causal-like masks: longest first).
     const int units = a.B * a.Hkv;
     const int id = blockIdx.x;
     const int xcd = id & 7, k = id >> 3;
@@ -71,15 +75,16 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
     const int unit = (k / per_unit) * 8 + xcd;
     if (unit >= units) return;
     const int rem = k % per_unit;
-    const int row = a.NR - 1 - rem / a.G;
     const int g = rem % a.G;
     const int b = unit / a.Hkv, hkv = unit % a.Hkv, hq = hkv * a.G + g;
+    const int64_t plane = (int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hq : 0);
+    const int row = a.kv_order ? ldc(a.kv_order + plane * a.NR + rem / a.G) : a.NR - 1 - rem / a.G;
 
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q_row = row * Bq + w * 32 + l32;
 
-    const int64_t line = ((int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hq : 0)) * a.NR + row;
+    const int64_t line = plane * a.NR + row;
     const int n_full = ldc(a.full_num + line), n_part = ldc(a.kv_num + line);
     const int T = (n_full + n_part) * a.sub;
 
@@ -125,7 +130,8 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
         }
     };
 
-    const ScoreMod<SCORE> smod(a.p, hq, a.scale);
+    const Score smod(a.p, hq, a.scale, lds_addr(s_rel));
+    smod.fill_table(tid, NW * 64);                  // visible after the prologue's barrier
     const int q_pos = q_ld + q_offset_of(a.p, b);   // as the mods see it
     const int q_wave_min = row * Bq + w * 32 + q_offset_of(a.p, b);   // the wave's rows: q_wave_min .. +31
     const MaskRow<MASK> mrow(a.p, b, hq, q_pos, a.kv_len);
@@ -193,7 +199,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
         const int dq0 = q_pos - kvs - 4 * half;
         const float abase = smod.alibi_base(dq0);
         auto rel = [&](int r) __attribute__((always_inline)) {
-            return typename ScoreMod<SCORE>::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3)));
+            return typename Score::RelPos(dq0, abase, -(8 * (r >> 2) + (r & 3)));
         };
         // relative bias: one value for the whole block unless it lies near the diagonal
         float rel_uni;

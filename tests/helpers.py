@@ -60,6 +60,7 @@ def library_mods(wl: wlm.Workload, inp, dev):
 
 BM_NAMES = ("kv_num_blocks", "kv_indices", "full_kv_num_blocks", "full_kv_indices",
             "q_num_blocks", "q_indices", "full_q_num_blocks", "full_q_indices")
+ORDER_NAMES = ("kv_order", "q_order")
 
 
 def assert_blockmask_equal(bm, ref):
@@ -67,6 +68,11 @@ def assert_blockmask_equal(bm, ref):
         got = getattr(bm, name).cpu()
         assert got.dtype == torch.int32 and got.shape == ref[name].shape, name
         assert torch.equal(got, ref[name]), name
+    for name in ORDER_NAMES:
+        if getattr(bm, name) is not None:
+            got = getattr(bm, name).cpu()
+            assert got.dtype == torch.int32 and got.shape == ref[name].shape, name
+            assert torch.equal(got, ref[name]), name
     if bm.stats is not None:
         st = bm.stats.cpu().tolist()
         assert st == [ref["stats"]["partial"], ref["stats"]["full"], ref["stats"]["total"],

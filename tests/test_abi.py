@@ -113,6 +113,7 @@ def test_blockmask_sizes_is_host_arithmetic():
     assert sz.kv_indices == sz.full_kv_indices == 6 * NR * NC
     assert sz.q_num_blocks == sz.full_q_num_blocks == 6 * NC
     assert sz.q_indices == sz.full_q_indices == 6 * NC * NR
+    assert sz.kv_order == 6 * NR and sz.q_order == 6 * NC
     assert lib.flexattn_blockmask_sizes(1, 1, 0, 64, 64, 64, C.byref(sz)) == fa.ERR_INVALID_ARG
     assert lib.flexattn_blockmask_sizes(1, 1, 64, 64, 64, 64, None) == fa.ERR_INVALID_ARG
     assert lib.flexattn_blockmask_sizes(64, 64, 1 << 20, 1 << 20, 64, 64, C.byref(sz)) == fa.ERR_UNSUPPORTED

@@ -126,6 +126,27 @@ def test_blockmask_without_full_blocks_gives_the_same_attention():
     check_grad("dV", dV, dV_ref)
 
 
+def test_work_order_changes_no_result():
+    """The BlockMask's work order decides which workgroup takes which row / column of blocks, nothing
+    else: with and without the order arrays every output is the same bit for bit."""
+    import paper_2412_05496_amd as fa
+    wl = SMALL["cfg3_small"]
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    O, LSE, bm, ids = run_forward(wl, inp, DEV)
+    assert bm.kv_order is not None and bm.q_order is not None
+    assert not torch.equal(bm.kv_order, torch.arange(bm.kv_order.shape[-1] - 1, -1, -1, device=DEV,
+                                                     dtype=torch.int32).expand_as(bm.kv_order))
+    grads = run_backward(wl, inp, DEV, O, LSE, bm, ids)
+    mask_id, score_id, params, Q, K, V = ids
+    bm.kv_order, bm.q_order = None, None
+    O2, LSE2 = torch.empty_like(O), torch.empty_like(LSE)
+    fa.flexattn_forward(Q, K, V, score_id, mask_id, params, bm, inp.scale, O2, LSE2)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2) and torch.equal(LSE, LSE2)
+    for g1, g2 in zip(grads, run_backward(wl, inp, DEV, O2, LSE2, bm, ids)):
+        assert torch.equal(g1, g2)
+
+
 def test_causal_row0_is_v0_bit_exact():
     wl = wlm.CFG1
     inp = wlm.make_train_inputs(wl)

@@ -224,3 +224,29 @@ def test_workload_generators_are_seeded_and_shaped():
     d = wlm.make_decode_inputs(wlm.CFG5.scaled(B=4, ctx_min=16, ctx_max=100, max_pages=8))
     used = [int(p) for b in range(4) for p in d.page_table[b, :(int(d.ctx_lens[b]) + 15) // 16]]
     assert len(set(used)) == len(used) == d.K_pool.shape[0]
+
+
+def test_work_order_is_longest_first_and_a_permutation():
+    """kv_order / q_order: per plane a permutation of the lines, descending number of listed blocks,
+    ties by ascending index -- checked against a plain Python sort, and for the causal mask against
+    the closed form (rows: last first; columns: first first)."""
+    import random
+    S, Bq, Bk = 1024, 128, 64
+    bm = fo.create_block_mask(fo.causal_mask, 1, 1, S, S, Bq, Bk)
+    NR, NC = S // Bq, S // Bk
+    assert bm["kv_order"].tolist() == [[list(range(NR - 1, -1, -1))]]
+    assert bm["q_order"][0, 0].tolist() == sorted(range(NC), key=lambda j: (-(NR - j // 2), j))
+    rng = random.Random(5)
+    doc = torch.tensor(sorted(rng.randrange(6) for _ in range(S)), dtype=torch.int32).view(1, S)
+    mask = fo.and_mask(fo.document_mask(doc), fo.causal_mask)
+    bm = fo.create_block_mask(mask, 1, 2, S, S, Bq, Bk)
+    for name, num, full in (("kv_order", "kv_num_blocks", "full_kv_num_blocks"),
+                            ("q_order", "q_num_blocks", "full_q_num_blocks")):
+        for h in range(2):
+            cnt = (bm[num][0, h] + bm[full][0, h]).tolist()
+            assert bm[name][0, h].tolist() == sorted(range(len(cnt)), key=lambda i: (-cnt[i], i)), name
+    # more lines than are sorted: the fixed orders
+    long_rows = fo.work_order(torch.zeros(1, 1, fo.WORK_ORDER_MAX_LINES + 1, dtype=torch.int32), True)
+    assert long_rows[0, 0, 0] == fo.WORK_ORDER_MAX_LINES and long_rows[0, 0, -1] == 0
+    long_cols = fo.work_order(torch.zeros(1, 1, fo.WORK_ORDER_MAX_LINES + 1, dtype=torch.int32), False)
+    assert long_cols[0, 0, 0] == 0 and long_cols[0, 0, -1] == fo.WORK_ORDER_MAX_LINES
