@@ -36,7 +36,7 @@ class Workload:
     Bq: int               # BlockMask block size along Q_LEN
     Bk: int               # BlockMask block size along KV_LEN
     mask: str             # "causal" | "doc_causal" | "swa_causal_or_prefix" | "ctx_len"
-    score: str            # "identity" | "softcap" | "alibi" | "rel_bias"
+    score: str            # "identity" | "softcap" | "alibi" | "rel_bias" | "alibi_softcap" | "rel_bias_softcap"
     seed: int
     backward: bool = True
     softcap: float = 0.0
@@ -143,9 +143,9 @@ def make_train_inputs(wl: Workload, with_dO: Optional[bool] = None) -> TrainInpu
             rows.append(document_ids(L))
         inp.doc_ids = torch.stack(rows).contiguous()
         inp.doc_lengths = lens
-    if wl.score == "alibi":
+    if "alibi" in wl.score:
         inp.slopes = alibi_slopes(wl.Hq)
-    if wl.score == "rel_bias":
+    if "rel_bias" in wl.score:
         inp.rel_bias = (torch.randn(wl.Hq, wl.rel_len, generator=gen, dtype=torch.float32) * 0.1).contiguous()
     return inp
 

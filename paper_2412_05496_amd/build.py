@@ -21,7 +21,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflexattn.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-NUM_VARIANTS = 10         # must equal kNumVariants in csrc/variants.h
+NUM_VARIANTS = 13         # must equal kNumVariants in csrc/variants.h
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Wno-unused-result", "-Wno-pass-failed",

@@ -5,13 +5,12 @@
 namespace flexattn {
 
 #define DECL(i) int bwd_launch_##i(const BwdArgs&, int, uint32_t, hipStream_t);
-DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8) DECL(9)
+FLEXATTN_VARIANT_INDICES(DECL)
 #undef DECL
 typedef int (*BwdLauncher)(const BwdArgs&, int, uint32_t, hipStream_t);
-static const BwdLauncher kBwdLaunchers[kNumVariants] = {bwd_launch_0, bwd_launch_1, bwd_launch_2,
-                                                        bwd_launch_3, bwd_launch_4, bwd_launch_5,
-                                                        bwd_launch_6, bwd_launch_7, bwd_launch_8,
-                                                        bwd_launch_9};
+#define ENTRY(i) bwd_launch_##i,
+static const BwdLauncher kBwdLaunchers[kNumVariants] = {FLEXATTN_VARIANT_INDICES(ENTRY)};
+#undef ENTRY
 int check_tensor(const flexattn_tensor* t);
 int check_extent(const flexattn_tensor* t, int len, int D);
 int check_problem(const flexattn_dims* d, const flexattn_blockmask* bm);

@@ -499,7 +499,11 @@ inline int check_canvas(uint32_t mask_id, const flexattn_mod_params* p, int q_le
     return (q_len == n && kv_len == n) ? FLEXATTN_OK : FLEXATTN_ERR_INVALID_ARG;
 }
 
-// The (mask, score) pairs that forward/backward kernels are instantiated for.
+// The (mask, score) pairs that forward/backward kernels are instantiated for: the paper's examples
+// and benchmark variants, and three compositions of them (sliding window with a soft-cap; nested
+// score_mods: ALiBi then soft-cap, relative bias then soft-cap under a document mask).  The functors
+// compose freely -- another pair is one more line here (and in the launcher lists that
+// FLEXATTN_VARIANT_INDICES drives), nothing else.
 // X(mask_id, score_id)
 #define FLEXATTN_FOR_EACH_VARIANT(X)                                                    \
     X(FLEXATTN_MASK_NONE, FLEXATTN_SCORE_IDENTITY)                                      \
@@ -511,6 +515,12 @@ inline int check_canvas(uint32_t mask_id, const flexattn_mod_params* p, int q_le
     X(FLEXATTN_MASK_DOCUMENT_CAUSAL, FLEXATTN_SCORE_IDENTITY)                           \
     X(FLEXATTN_MASK_DOCUMENT_CAUSAL, FLEXATTN_SCORE_ALIBI)                              \
     X(FLEXATTN_MASK_SWA_CAUSAL_OR_PREFIX, FLEXATTN_SCORE_REL_BIAS)                      \
-    X(FLEXATTN_MASK_NEIGHBORHOOD, FLEXATTN_SCORE_IDENTITY)
+    X(FLEXATTN_MASK_NEIGHBORHOOD, FLEXATTN_SCORE_IDENTITY)                              \
+    X(FLEXATTN_MASK_SWA_CAUSAL, FLEXATTN_SCORE_SOFTCAP)                                 \
+    X(FLEXATTN_MASK_CAUSAL, (FLEXATTN_SCORE_ALIBI | FLEXATTN_SCORE_SOFTCAP))            \
+    X(FLEXATTN_MASK_DOCUMENT_CAUSAL, (FLEXATTN_SCORE_REL_BIAS | FLEXATTN_SCORE_SOFTCAP))
+
+// One entry per line of FLEXATTN_FOR_EACH_VARIANT: X(index)
+#define FLEXATTN_VARIANT_INDICES(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12)
 
 }  // namespace flexattn

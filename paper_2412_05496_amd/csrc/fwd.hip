@@ -5,19 +5,18 @@
 namespace flexattn {
 
 #define DECL(i) int fwd_launch_##i(const FwdArgs&, int, int, hipStream_t);
-DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8) DECL(9)
+FLEXATTN_VARIANT_INDICES(DECL)
 #undef DECL
 typedef int (*FwdLauncher)(const FwdArgs&, int, int, hipStream_t);
-static const FwdLauncher kFwdLaunchers[kNumVariants] = {fwd_launch_0, fwd_launch_1, fwd_launch_2,
-                                                        fwd_launch_3, fwd_launch_4, fwd_launch_5,
-                                                        fwd_launch_6, fwd_launch_7, fwd_launch_8,
-                                                        fwd_launch_9};
+#define ENTRY(i) fwd_launch_##i,
+static const FwdLauncher kFwdLaunchers[kNumVariants] = {FLEXATTN_VARIANT_INDICES(ENTRY)};
+#undef ENTRY
 #define DECL(i) int fwd_paged_launch_##i(const FwdArgs&, int, int, hipStream_t);
-DECL(0) DECL(1) DECL(2) DECL(3) DECL(4) DECL(5) DECL(6) DECL(7) DECL(8) DECL(9)
+FLEXATTN_VARIANT_INDICES(DECL)
 #undef DECL
-static const FwdLauncher kFwdPagedLaunchers[kNumVariants] = {
-    fwd_paged_launch_0, fwd_paged_launch_1, fwd_paged_launch_2, fwd_paged_launch_3, fwd_paged_launch_4,
-    fwd_paged_launch_5, fwd_paged_launch_6, fwd_paged_launch_7, fwd_paged_launch_8, fwd_paged_launch_9};
+#define ENTRY(i) fwd_paged_launch_##i,
+static const FwdLauncher kFwdPagedLaunchers[kNumVariants] = {FLEXATTN_VARIANT_INDICES(ENTRY)};
+#undef ENTRY
 
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(int e) { g_last_hip_error = e; }

@@ -223,7 +223,11 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
                 for (int r = 0; r < 16; ++r) s[r] = keep(kvs + crow(r, half)) ? s[r] : 0.0f;
             }
         } else {
-            if (rel_is_uni) {
+            // A score_mod that only scales (the identity): the factor is positive, so the maximum can be
+            // taken over the raw dot products and the scaling folded into the exponent's multiply-add.
+            constexpr bool kScaleOnly = SCORE == FLEXATTN_SCORE_IDENTITY;
+            if constexpr (kScaleOnly) {
+            } else if (rel_is_uni) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[r] = smod.template apply<true>(s[r], rel(r), rel_uni);
             } else {
@@ -239,12 +243,14 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
             mx = fmaxf(mx, swap_halves(mx));
+            if constexpr (kScaleOnly) mx *= smod.k_acc;
             const float m_new = fmaxf(m_run, mx);
             const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
             const float alpha = fast_exp2(m_run - m_use);
             m_run = m_new;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r] - m_use);
+            for (int r = 0; r < 16; ++r)
+                s[r] = fast_exp2(kScaleOnly ? __builtin_fmaf(s[r], smod.k_acc, -m_use) : s[r] - m_use);
             l_run *= alpha;
             if (__any(alpha != 1.0f)) {
 #pragma unroll

@@ -15,7 +15,10 @@ struct Variant {
 constexpr Variant kVariants[] = {FLEXATTN_FOR_EACH_VARIANT(FLEXATTN_VARIANT_ENTRY)};
 #undef FLEXATTN_VARIANT_ENTRY
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-static_assert(kNumVariants == 10, "update the launcher declarations in fwd.hip / bwd.hip and the build list");
+#define FLEXATTN_COUNT_ONE(i) +1
+static_assert(kNumVariants == 0 FLEXATTN_VARIANT_INDICES(FLEXATTN_COUNT_ONE),
+              "FLEXATTN_VARIANT_INDICES (flex_common.h) and NUM_VARIANTS (build.py) must list every variant");
+#undef FLEXATTN_COUNT_ONE
 
 inline int find_variant(uint32_t mask, uint32_t score) {
     for (int i = 0; i < kNumVariants; ++i)

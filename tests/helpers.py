@@ -35,6 +35,10 @@ def oracle_mods(wl: wlm.Workload, inp):
         score = fo.Alibi(-inp.slopes.double())          # score - slope_h * (q - kv)
     elif wl.score == "rel_bias":
         score = fo.RelBias(inp.rel_bias.double())
+    elif wl.score == "alibi_softcap":               # nested score_mods: the bias first, then the soft-cap
+        score = fo.Compose(fo.Alibi(-inp.slopes.double()), fo.Softcap(wl.softcap))
+    elif wl.score == "rel_bias_softcap":
+        score = fo.Compose(fo.RelBias(inp.rel_bias.double()), fo.Softcap(wl.softcap))
     else:
         raise ValueError(wl.score)
     return score, mask
@@ -46,7 +50,8 @@ def library_mods(wl: wlm.Workload, inp, dev):
                "swa_causal": fa.MASK_SWA_CAUSAL, "prefix_lm": fa.MASK_PREFIX_LM,
                "swa_causal_or_prefix": fa.MASK_SWA_CAUSAL_OR_PREFIX}[wl.mask]
     score_id = {"identity": fa.SCORE_IDENTITY, "softcap": fa.SCORE_SOFTCAP, "alibi": fa.SCORE_ALIBI,
-                "rel_bias": fa.SCORE_REL_BIAS}[wl.score]
+                "rel_bias": fa.SCORE_REL_BIAS, "alibi_softcap": fa.SCORE_ALIBI | fa.SCORE_SOFTCAP,
+                "rel_bias_softcap": fa.SCORE_REL_BIAS | fa.SCORE_SOFTCAP}[wl.score]
     params = fa.ModParams(window=wl.window, prefix_len=wl.prefix_len, softcap=wl.softcap)
     if inp.doc_ids is not None:
         params.doc_ids = inp.doc_ids.to(dev)

@@ -39,6 +39,8 @@ def test_supported_variants():
     assert fa.flexattn_is_supported(fa.MASK_CAUSAL, fa.SCORE_SOFTCAP, 128)
     assert fa.flexattn_is_supported(fa.MASK_DOCUMENT_CAUSAL, fa.SCORE_ALIBI, 64)
     assert fa.flexattn_is_supported(fa.MASK_SWA_CAUSAL_OR_PREFIX, fa.SCORE_REL_BIAS, 128)
+    assert fa.flexattn_is_supported(fa.MASK_SWA_CAUSAL, fa.SCORE_SOFTCAP, 128)
+    assert fa.flexattn_is_supported(fa.MASK_CAUSAL, fa.SCORE_ALIBI | fa.SCORE_SOFTCAP, 64)
     assert not fa.flexattn_is_supported(fa.MASK_CAUSAL, fa.SCORE_SOFTCAP, 96)
     assert not fa.flexattn_is_supported(fa.MASK_CTX_LEN, fa.SCORE_REL_BIAS | fa.SCORE_SOFTCAP, 128)
 

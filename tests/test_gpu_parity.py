@@ -43,6 +43,14 @@ SMALL = {
                                        score="softcap", seed=18, softcap=30.0),
     "prefix_lm_d64": wlm.Workload("prefix64", B=1, Hq=2, Hkv=1, S=1024, D=64, Bq=128, Bk=64, mask="prefix_lm",
                                   score="identity", seed=19, prefix_len=300),
+    # compositions: a sliding window with a soft-cap; nested score_mods (bias, then soft-cap)
+    "swa_softcap_d128": wlm.Workload("swa_cap", B=1, Hq=4, Hkv=2, S=1024, D=128, Bq=128, Bk=64, mask="swa_causal",
+                                     score="softcap", seed=23, window=300, softcap=30.0),
+    "causal_alibi_softcap_d64": wlm.Workload("alibi_cap", B=1, Hq=4, Hkv=4, S=768, D=64, Bq=128, Bk=64,
+                                             mask="causal", score="alibi_softcap", seed=24, softcap=20.0),
+    "doc_relbias_softcap_d128": wlm.Workload("rel_cap", B=2, Hq=2, Hkv=1, S=640, D=128, Bq=64, Bk=64,
+                                             mask="doc_causal", score="rel_bias_softcap", seed=25, softcap=50.0,
+                                             rel_len=96, doc_len_min=60, doc_len_max=300),
     "softcap_unbounded_d128": wlm.Workload("softcap_big", B=1, Hq=2, Hkv=2, S=512, D=128, Bq=128, Bk=64, mask="causal",
                                            score="softcap", seed=20, softcap=50.0),
 }
