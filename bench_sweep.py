@@ -1,10 +1,10 @@
 """Sweep over the shapes of the paper's kernel benchmarks (section 6.2: head dimension 64, KV size fixed
 at 256 MiB, causal attention from 1k to 64k tokens; seven variants at 16k tokens with and without GQA;
-section 4.2: the full / partial split; section 6.2 / 6.4: decode from 1k to 132k tokens and page sizes;
+section 4.2: the full / partial split; section 6.2 / 6.4: decode from 1k to 132k tokens, small batches, page sizes 16 .. 256;
 sections 5.1 + 5.2: a chunk of query tokens against a paged cache, beside the same chunk on a contiguous cache;
 appendix: neighborhood attention in row-major, tiled and Morton token order over canvas and kernel sizes).
 
-    python bench_sweep.py [--part train|variants|split|decode|pages|prefill|na|all] [--iters N]
+    python bench_sweep.py [--part train|variants|split|decode|batch|pages|prefill|na|all] [--iters N]
 
 One JSON line per measured point (synthetic seeded inputs, bf16, one MI355X).  TFLOP/s count UNMASKED
 FLOPs only (4 D per pair forward, 10 D backward); decode is HBM GB/s of the K/V bytes of the tokens read.
@@ -26,7 +26,8 @@ if ROOT not in sys.path:
 def event_ms(fn, iters):
     import torch
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    fn()
+    for _ in range(3):      # warm-up
+        fn()
     torch.cuda.synchronize()
     start.record()
     for _ in range(iters):
@@ -173,7 +174,7 @@ def na_point(fa, wlm, canvas, kernel, layout, tile, iters, dev):
 
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--part", default="all", choices=["train", "variants", "split", "decode", "pages", "prefill", "na", "all"])
+    ap.add_argument("--part", default="all", choices=["train", "variants", "split", "decode", "batch", "pages", "prefill", "na", "all"])
     ap.add_argument("--iters", type=int, default=10)
     args = ap.parse_args()
 
@@ -184,7 +185,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     W = wlm.Workload
-    parts = [args.part] if args.part != "all" else ["train", "variants", "split", "decode", "pages", "prefill", "na"]
+    parts = [args.part] if args.part != "all" else ["train", "variants", "split", "decode", "batch", "pages", "prefill", "na"]
 
     if "train" in parts:        # causal, D = 64, H = 16, B * S = 65536 (K + V = 256 MiB)
         for S in (1024, 2048, 4096, 8192, 16384, 32768, 65536):
@@ -213,8 +214,14 @@ def main() -> int:
                    seed=2300 + ctx // 1024, backward=False, page_size=16, ctx_min=ctx, ctx_max=ctx,
                    max_pages=ctx // 16)
             decode_point(fa, wlm, wl, args.iters, "decode", dev)
-    if "pages" in parts:        # page size 16 .. 128, scattered pages against a contiguous cache
-        for page in (16, 32, 64, 128):
+    if "batch" in parts:        # few sequences: the split length follows the batch so that the chip stays full
+        for nseq, ctx in ((1, 8192), (1, 32768), (1, 131072), (4, 8192), (4, 32768), (16, 8192), (16, 32768)):
+            wl = W(f"sweep_batch_{nseq}x{ctx}", B=nseq, Hq=32, Hkv=8, S=1, D=128, Bq=1, Bk=16, mask="ctx_len",
+                   score="identity", seed=2350 + nseq + ctx // 1024, backward=False, page_size=16, ctx_min=ctx,
+                   ctx_max=ctx, max_pages=ctx // 16)
+            decode_point(fa, wlm, wl, args.iters, "batch", dev)
+    if "pages" in parts:        # page size 16 .. 256, scattered pages against a contiguous cache
+        for page in (16, 32, 64, 128, 256):
             for ident in (False, True):
                 wl = W(f"sweep_pages_{page}", B=64, Hq=32, Hkv=8, S=1, D=128, Bq=1, Bk=page, mask="ctx_len",
                        score="identity", seed=2400 + page, backward=False, page_size=page, ctx_min=16384,

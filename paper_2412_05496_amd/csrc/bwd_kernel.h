@@ -106,6 +106,9 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const BwdArgs a) {
 // Q / dO tiles and the per-row scalars are double buffered in LDS; the loads of step v+1 are
 // issued at the top of step v.  Two barriers per step: after the exchange writes, and at the end
 // (exchange buffer and ring slot free again, next tiles landed).
+// M0 RULE: this kernel fills LDS through the LDS-DMA helpers of lds_tiles.h, which write M0 behind the
+// compiler's back.  Keep every register array in it indexed by compile-time constants (no movrel /
+// s_set_gpr_idx code, which would also use M0) and add no other LDS-DMA or M0-based construct.
 template <int D, uint32_t MASK, uint32_t SCORE>
 __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv_kernel(const BwdArgs a) {
     constexpr int TQ = 64;                         // query rows per step
@@ -412,6 +415,9 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
 // for the relative bias (the factor ScoreMod::grad_scale() is applied by the reduction that follows).
 // One partial result per workgroup; the blocks whose every pair falls on the table's last (or first)
 // entry are summed in registers, the others entry by entry with LDS atomics.
+// M0 RULE: this kernel fills LDS through the LDS-DMA helpers of lds_tiles.h, which write M0 behind the
+// compiler's back.  Keep every register array in it indexed by compile-time constants (no movrel /
+// s_set_gpr_idx code, which would also use M0) and add no other LDS-DMA or M0-based construct.
 template <int D, int NW, uint32_t MASK, uint32_t SCORE, bool CAPTURED = false>
 __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_dq_kernel(const BwdArgs a) {
     constexpr int Bq = NW * 32;

@@ -28,7 +28,7 @@ constexpr int kDecWaves = 4;       // waves per workgroup (the mapping below ass
 constexpr int kDecTile = 32;       // keys per inner tile
 constexpr int kDecSplitMax = 1024; // keys per split: a power of two in [kDecSplitMin, kDecSplitMax],
 constexpr int kDecSplitMin = 128;  // chosen by the host so that the launch fills the chip (split_len_of)
-constexpr int kDecResidentWaves = 256 * 8;   // waves the chip holds at once: 256 CUs x 2 workgroups x 4
+constexpr int kDecTargetWaves = 256 * 4;   // one wave per SIMD: finer cuts cost more per-wave start-up than they gain
 
 struct DecodeArgs {
     const bf16* Q;
@@ -51,6 +51,9 @@ struct DecodeArgs {
     float* LSE;
 };
 
+// M0 RULE: this kernel fills LDS through the LDS-DMA helpers of lds_tiles.h, which write M0 behind the
+// compiler's back.  Keep every register array in it indexed by compile-time constants (no movrel /
+// s_set_gpr_idx code, which would also use M0) and add no other LDS-DMA or M0-based construct.
 template <int D, uint32_t SCORE>
 __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const DecodeArgs a) {
     constexpr int DC = D / 8;                  // 16-byte chunks per row
@@ -266,11 +269,12 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
 // Keys per split.  One wave works on one (sequence, KV head, split), so a launch offers
 // nseq * Hkv * ceil(ctx / split_len) waves; the host cannot see the context lengths and sizes the
 // split for the longest context the page table addresses: the largest power of two in
-// [kDecSplitMin, kDecSplitMax] that still gives the chip one wave per slot, so that a small batch
-// of long sequences is cut finer than a large one.
+// [kDecSplitMin, kDecSplitMax] that still gives every SIMD of the chip a wave, so that a small batch
+// of long sequences is cut finer than a large one (measured: aiming at two waves per SIMD instead
+// makes one sequence of 32k tokens 1.5x slower -- each wave's start-up outweighs its 128 keys).
 static int split_len_of(const flexattn_decode_dims* d) {
     const long long max_tokens = (long long)d->max_pages * d->page_size;
-    const long long per_wave = max_tokens * d->nseq * d->Hkv / kDecResidentWaves;
+    const long long per_wave = max_tokens * d->nseq * d->Hkv / kDecTargetWaves;
     int len = kDecSplitMin;
     while (len < kDecSplitMax && 2 * len <= per_wave) len *= 2;
     return len;

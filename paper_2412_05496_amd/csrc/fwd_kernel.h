@@ -55,6 +55,9 @@ constexpr int kTileKV = 64;   // keys per kernel tile
 // softmax maximum (see ScoreMod::bounded); chosen by the host from the cap value.
 // PAGED: the tiles of K and V are fetched from a paged pool through the converted block lists;
 // the mods keep seeing the logical key index.
+// M0 RULE: this kernel fills LDS through the LDS-DMA helpers of lds_tiles.h, which write M0 behind the
+// compiler's back.  Keep every register array in it indexed by compile-time constants (no movrel /
+// s_set_gpr_idx code, which would also use M0) and add no other LDS-DMA or M0-based construct.
 template <int D, int NW, uint32_t MASK, uint32_t SCORE, bool BOUNDED, bool PAGED = false>
 __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void fwd_kernel(const FwdArgs a) {
     constexpr int Bq = NW * 32;

@@ -59,21 +59,23 @@ __global__ __launch_bounds__(256, 2) void probe_mfma_kernel(float* sink, long lo
 #pragma unroll
         for (int u = 0; u < kProbeUnroll; ++u) {
             acc[u & 3] = mfma32(x[u & 3], y[(u >> 2) & 3], acc[u & 3]);
-            if constexpr (VALU_MIX == 2) {
-                float& a = v[(2 * u) & 7];
-                float& b = v[(2 * u + 1) & 7];
-                asm volatile("v_fma_f32 %0, %0, %2, %3\n\tv_exp_f32 %1, %1\n\tv_fma_f32 %0, %0, %2, %3\n\t"
-                             "v_rcp_f32 %1, %1\n\tv_fma_f32 %0, %0, %2, %3"
-                             : "+v"(a), "+v"(b) : "v"(c0), "v"(c1));
+            // Vector work behind the MFMA: each instruction on another register (eight values in rotation),
+            // so that no instruction waits for the one before it.  (asm: the compiler must neither fold
+            // nor regroup these.)
+            if constexpr (VALU_MIX == 1) {      // forward: 4 multiply-adds, 3 transcendentals
+                asm volatile("v_fma_f32 %0, %0, %8, %9\n\tv_exp_f32 %1, %1\n\tv_fma_f32 %2, %2, %8, %9\n\t"
+                             "v_rcp_f32 %3, %3\n\tv_fma_f32 %4, %4, %8, %9\n\tv_exp_f32 %5, %5\n\t"
+                             "v_fma_f32 %6, %6, %8, %9"
+                             : "+v"(v[(u + 0) & 7]), "+v"(v[(u + 1) & 7]), "+v"(v[(u + 2) & 7]), "+v"(v[(u + 3) & 7]),
+                               "+v"(v[(u + 4) & 7]), "+v"(v[(u + 5) & 7]), "+v"(v[(u + 6) & 7]), "+v"(v[(u + 7) & 7])
+                             : "v"(c0), "v"(c1));
             }
-            if constexpr (VALU_MIX == 1) {
-                float& a = v[(2 * u) & 7];
-                float& b = v[(2 * u + 1) & 7];
-                // (asm: the compiler must neither fold nor regroup these)
-                asm volatile("v_fma_f32 %0, %0, %2, %3\n\tv_exp_f32 %1, %1\n\tv_fma_f32 %0, %0, %2, %3\n\t"
-                             "v_rcp_f32 %1, %1\n\tv_fma_f32 %0, %0, %2, %3\n\tv_exp_f32 %1, %1\n\t"
-                             "v_fma_f32 %1, %1, %2, %3"
-                             : "+v"(a), "+v"(b) : "v"(c0), "v"(c1));
+            if constexpr (VALU_MIX == 2) {      // backward: 3 multiply-adds, 2 transcendentals
+                asm volatile("v_fma_f32 %0, %0, %5, %6\n\tv_exp_f32 %1, %1\n\tv_fma_f32 %2, %2, %5, %6\n\t"
+                             "v_rcp_f32 %3, %3\n\tv_fma_f32 %4, %4, %5, %6"
+                             : "+v"(v[(u + 0) & 7]), "+v"(v[(u + 1) & 7]), "+v"(v[(u + 2) & 7]), "+v"(v[(u + 3) & 7]),
+                               "+v"(v[(u + 4) & 7])
+                             : "v"(c0), "v"(c1));
             }
         }
         // fold the accumulators back now and then so that random operands never reach infinity

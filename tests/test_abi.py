@@ -134,7 +134,8 @@ def test_decode_workspace_follows_the_split_length():
 
     assert ws(64, 32, 8, 128, 16, 2048) == 64 * 32 * 32 * 130 * 4          # config 5: 32 splits of 1024
     assert ws(1, 32, 8, 128, 16, 512) == 1 * 32 * 64 * 130 * 4             # 8192 tokens, 8 heads: 128-key splits
-    assert ws(4, 8, 8, 64, 256, 128) == 4 * 8 * 64 * 66 * 4                # 32768 tokens x 32 units: 512-key splits
+    assert ws(1, 32, 8, 128, 16, 2048) == 1 * 32 * 128 * 130 * 4           # 32768 tokens, 8 heads: 256-key splits
+    assert ws(4, 8, 8, 64, 256, 128) == 4 * 8 * 32 * 66 * 4                # 32768 tokens x 32 units: 1024-key splits
     assert ws(2, 4, 2, 64, 16, 4) == 2 * 4 * 1 * 66 * 4                    # shorter than one split
     assert ws(2, 4, 2, 64, 24, 4) == 0 and ws(2, 4, 2, 64, 2048, 4) == 0   # page sizes that are refused
     assert ws(2, 4, 2, 64, 8, 4) == 0
