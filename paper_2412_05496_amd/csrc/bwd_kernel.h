@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
     int col = slot / sub_k;
     if (a.q_order) {
         const int64_t plane0 = (int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hkv * a.G : 0);
-        col = a.q_order[plane0 * a.NC + col];
+        col = min(max(a.q_order[plane0 * a.NC + col], 0), a.NC - 1);   // clamped: a bad order array stays inside the lists
     }
     const int tile = col * sub_k + slot % sub_k;
     const int kv0 = tile * 64;
@@ -436,7 +436,7 @@ __global__ __launch_bounds__(NW * 64, (bwd_waves_per_simd<D, MASK>())) void bwd_
     const int g = rem % a.G;
     const int b = unit / a.Hkv, hkv = unit % a.Hkv, hq = hkv * a.G + g;
     const int64_t plane = (int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hq : 0);
-    const int row = a.kv_order ? ldc(a.kv_order + plane * a.NR + rem / a.G) : a.NR - 1 - rem / a.G;
+    const int row = a.kv_order ? min(max(ldc(a.kv_order + plane * a.NR + rem / a.G), 0), a.NR - 1) : a.NR - 1 - rem / a.G;
 
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -81,7 +81,8 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
     const int g = rem % a.G;
     const int b = unit / a.Hkv, hkv = unit % a.Hkv, hq = hkv * a.G + g;
     const int64_t plane = (int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hq : 0);
-    const int row = a.kv_order ? ldc(a.kv_order + plane * a.NR + rem / a.G) : a.NR - 1 - rem / a.G;
+    // (an order array that is no permutation gives wrong rows; clamped so that it cannot leave the arrays)
+    const int row = a.kv_order ? min(max(ldc(a.kv_order + plane * a.NR + rem / a.G), 0), a.NR - 1) : a.NR - 1 - rem / a.G;
 
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
