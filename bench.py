@@ -5,7 +5,10 @@
 One step = BlockMask build + forward + backward (all three through the C ABI) on the dense
 causal + tanh-softcap training shape B=4, H=16, S=8192, D=128 (bf16, synthetic N(0,1) inputs
 resident in HBM).  `value` is TFLOP/s over UNMASKED FLOPs only: 4*D per unmasked (q, kv) pair for
-the forward, 10*D for the backward (five GEMMs; recomputation is not credited).
+the forward, 10*D for the backward (five GEMMs; recomputation is not credited).  The step's
+backward is flexattn_backward_stored -- dS written to HBM by the dK/dV kernel and read back by a lean
+dQ kernel, 4.4 GB of workspace -- which is the faster of the library's two on this shape; the
+recomputing flexattn_backward is timed in the same run (`bwd_recompute`).
 
 The JSON line also carries
   roofline      the longest kernel of the step against the dense bf16 MFMA peak, timed with
@@ -89,10 +92,19 @@ def train_leg(fa, wlm, wl, dev, iters: int, mfma_tflops: float) -> dict:
     t_dq = event_time_ms(lambda: bwd(fa.BWD_DQ), iters)
     partial, full, total, unmasked = bm.stats.cpu().tolist()
     pairs = unmasked * (wl.B // Bm) * wl.Hq
+    # the backward that keeps dS in memory, for comparison (it pays where the head dimension is large
+    # and the score_mod costly; the figures of this leg are those of the recomputing backward)
+    st_ws = torch.empty(fa.flexattn_backward_stored_workspace_bytes(Q, Kt, bm, partial + full), dtype=torch.uint8,
+                        device=dev)
+    bwd_st = lambda: fa.flexattn_backward_stored(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale,
+                                                 dQ, dK, dV, partial + full, st_ws)
+    bwd_st()
+    t_st = event_time_ms(bwd_st, iters)
     f_f, f_b = 4 * wl.D * pairs / (t_f * 1e-3) / 1e12, 10 * wl.D * pairs / (t_b * 1e-3) / 1e12
     leg = {
         "workload": wl.name, "pairs": pairs, "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4),
         "bwd_dkdv_ms": round(t_dkdv, 4), "bwd_dq_ms": round(t_dq, 4),
+        "bwd_with_dS_in_memory_ms": round(t_st, 4), "bwd_with_dS_in_memory_workspace_gb": round(st_ws.numel() / 1e9, 2),
         "fwd_tflops": round(f_f, 1), "bwd_tflops": round(f_b, 1),
         "fwd_frac_of_bf16_peak": round(f_f / PEAK_BF16_TFLOPS, 4),
         "bwd_frac_of_bf16_peak": round(f_b / PEAK_BF16_TFLOPS, 4),
@@ -156,6 +168,10 @@ def main() -> int:
     LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=dev)
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Kt), torch.empty_like(V)
     bwd_ws = torch.empty(fa.flexattn_backward_workspace_bytes(Q, Kt), dtype=torch.uint8, device=dev)
+    # The step's backward keeps dS in memory (flexattn_backward_stored: 5 GEMMs and 2 bytes of HBM
+    # traffic each way per unmasked score); the recomputing one (7 GEMMs) is timed beside it.
+    n_blocks = sum((r + 1) * wl.Bq // wl.Bk for r in range(wl.S // wl.Bq))   # causal, closed form; checked against stats below
+    st_ws = torch.empty(fa.flexattn_backward_stored_workspace_bytes(Q, Kt, bm, n_blocks), dtype=torch.uint8, device=dev)
 
     def build():
         fa.flexattn_blockmask_build(mask_id, params, bm, bm_ws)
@@ -163,9 +179,13 @@ def main() -> int:
     def fwd():
         fa.flexattn_forward(Q, Kt, V, score_id, mask_id, params, bm, inp.scale, O, LSE)
 
-    def bwd(stages=fa.BWD_ALL):
+    def bwd_recompute(stages=fa.BWD_ALL):
         fa.flexattn_backward_stages(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV,
                                     bwd_ws, stages)
+
+    def bwd(stages=fa.BWD_ALL):
+        fa.flexattn_backward_stored(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV,
+                                    n_blocks, st_ws, stages)
 
     def step():
         build()
@@ -184,6 +204,7 @@ def main() -> int:
     pairs = wl.B * wl.Hq * wl.S * (wl.S + 1) // 2
     stats = bm.stats.cpu().tolist()
     assert stats[3] * wl.B * wl.Hq == pairs, "BlockMask unmasked-pair count disagrees with the closed form"
+    assert stats[0] + stats[1] == n_blocks, "BlockMask block count disagrees with the closed form"
     flops_fwd, flops_bwd = 4 * wl.D * pairs, 10 * wl.D * pairs
     value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
 
@@ -195,15 +216,20 @@ def main() -> int:
         "bwd_dkdv": event_time_ms(lambda: bwd(fa.BWD_DKDV), K),
         "bwd_dq": event_time_ms(lambda: bwd(fa.BWD_DQ), K),
     }
-    # algorithmic FLOPs per launch: forward 4*D*pairs; the backward's 10*D*pairs is split between
-    # its two MFMA kernels in proportion to the GEMMs each must execute (dK/dV: 4 of 7, dQ: 3 of 7)
-    alg = {"fwd": flops_fwd, "bwd_dkdv": flops_bwd * 4 / 7, "bwd_dq": flops_bwd * 3 / 7}
+    # algorithmic FLOPs per launch: forward 4*D*pairs; of the backward's 10*D*pairs (five GEMMs) the
+    # dK/dV kernel executes four GEMMs and the dQ kernel one -- nothing is computed twice
+    alg = {"fwd": flops_fwd, "bwd_dkdv": flops_bwd * 4 / 5, "bwd_dq": flops_bwd * 1 / 5}
     dom = max(alg, key=lambda k: kt[k])
     achieved = alg[dom] / (kt[dom] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(dom),
                 "avg_ms": round(kt[dom], 4)}
     bwd_ms = kt["bwd_delta"] + kt["bwd_dkdv"] + kt["bwd_dq"]
+    # the recomputing backward (flexattn_backward): no extra workspace, S and dP computed in both kernels
+    kr = {"bwd_delta": event_time_ms(lambda: bwd_recompute(fa.BWD_DELTA), K),
+          "bwd_dkdv": event_time_ms(lambda: bwd_recompute(fa.BWD_DKDV), K),
+          "bwd_dq": event_time_ms(lambda: bwd_recompute(fa.BWD_DQ), K)}
+    bwd_rec_ms = sum(kr.values())
     out = {
         "metric": "flex_attention fwd+bwd TFLOP/s (unmasked FLOPs), dense causal + softcap",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -211,12 +237,17 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "H": wl.Hq, "S": wl.S, "D": wl.D, "mask": "causal",
                    "score_mod": "tanh softcap 30", "block": f"{wl.Bq}x{wl.Bk}",
-                   "step": "blockmask_build + forward + backward"},
+                   "step": "blockmask_build + forward + backward (dS kept in memory)"},
         "fwd_tflops": round(flops_fwd / (kt["fwd"] * 1e-3) / 1e12, 2),
         "fwd_frac_of_bf16_peak": round(flops_fwd / (kt["fwd"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "bwd_tflops": round(flops_bwd / (bwd_ms * 1e-3) / 1e12, 2),
         "bwd_frac_of_bf16_peak": round(flops_bwd / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "kernel_ms": {k: round(v, 4) for k, v in kt.items()},
+        "bwd_workspace_gb": round(st_ws.numel() / 1e9, 2),
+        "bwd_recompute": {"what": "flexattn_backward: dQ recomputes S and dP (7 GEMMs for the 5 credited), 4 MB workspace",
+                          "kernel_ms": {k: round(v, 4) for k, v in kr.items()}, "bwd_ms": round(bwd_rec_ms, 4),
+                          "bwd_tflops": round(flops_bwd / (bwd_rec_ms * 1e-3) / 1e12, 2),
+                          "bwd_frac_of_bf16_peak": round(flops_bwd / (bwd_rec_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
         "blockmask": {"partial": stats[0], "full": stats[1], "total": stats[2]},
         "roofline": roofline,
     }
@@ -252,10 +283,9 @@ def main() -> int:
         "mfma_with_softcap_valu_mix_tflops_constant_operands": round(mix_const, 1),
         "mfma_with_softcap_bwd_valu_mix_tflops": round(bwd_mix_random, 1),
         "mfma_with_softcap_bwd_valu_mix_core_ghz": round(ghz_bwd_mix, 3),
-        # what the two stall-free instruction streams would give in credited FLOPs (the backward
-        # executes 7 GEMMs for the 5 it is credited with)
+        # the two MFMA kernels against the stall-free instruction streams of their hot loops
         "fwd_frac_of_stall_free_mix": round(out["fwd_tflops"] / mix_random, 4),
-        "bwd_frac_of_stall_free_mix": round(out["bwd_tflops"] / (bwd_mix_random * 5 / 7), 4),
+        "bwd_dkdv_frac_of_stall_free_mix": round(alg["bwd_dkdv"] / (kt["bwd_dkdv"] * 1e-3) / 1e12 / bwd_mix_random, 4),
         "stream_read_gbs": round(read_gbs, 1),
         "how": "flexattn_probe_mfma: nothing but 32x32x16 bf16 MFMAs on register operands, 2 waves per SIMD, "
                "operands of random sign / exponent / mantissa (the chip clocks lower the more the operands toggle: "

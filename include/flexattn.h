@@ -268,6 +268,36 @@ int flexattn_backward_stages(const flexattn_dims* dims,
                              const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
                              void* ws, size_t ws_bytes, void* stream, uint32_t stages);
 
+/* The same gradients with dS kept in device memory instead of being recomputed (a trade of HBM
+ * capacity and bandwidth for arithmetic; the result is as deterministic as flexattn_backward's, and
+ * equal to it up to the rounding of dS to bf16, which both take before the dQ and dK products).
+ * The dK/dV kernel writes the gradient of the scores of every non-empty block it visits (section
+ * 4.2's transposed walk) and dQ = scale * dS K is then one block-sparse product over the written
+ * blocks: the backward executes the five matrix products of its definition instead of seven.
+ *   n_blocks  capacity, in blocks of Bq x Bk scores: at least the number of non-empty (PARTIAL +
+ *             FULL) blocks of the BlockMask, all planes together -- stats[0] + stats[1] of
+ *             flexattn_blockmask_build.  A smaller value gives wrong gradients for the blocks that
+ *             do not fit (slots are clamped; nothing is accessed outside the workspace).
+ *   ws        device workspace, 256-byte aligned, of flexattn_backward_stored_workspace_bytes()
+ *             bytes: the row scalars, one int32 per block position of the BlockMask grid, and
+ *             2 * Bq * Bk bytes per block and per head that does not share the BlockMask plane with
+ *             an equal (b, hq) -- B * Hq * n_blocks blocks for a broadcast BlockMask (config 2:
+ *             64 heads x 4160 blocks x 16 KiB = 4.4 GB).  Returns 0 for invalid arguments.
+ *   stages    as in flexattn_backward_stages (FLEXATTN_BWD_ALL for the whole backward): DELTA also
+ *             numbers the blocks and must have run on the workspace first; DKDV writes dK, dV and
+ *             the dS blocks; DQ reads them, so it must follow DKDV on the same workspace.
+ * All other arguments and errors as flexattn_backward.
+ */
+size_t flexattn_backward_stored_workspace_bytes(const flexattn_dims* dims, const flexattn_blockmask* bm,
+                                                int64_t n_blocks);
+int flexattn_backward_stored(const flexattn_dims* dims,
+                             const flexattn_tensor* Q, const flexattn_tensor* K, const flexattn_tensor* V,
+                             const flexattn_tensor* O, const flexattn_tensor* dO, const float* LSE,
+                             uint32_t score_id, uint32_t mask_id, const flexattn_mod_params* params,
+                             const flexattn_blockmask* bm, float scale,
+                             const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
+                             int64_t n_blocks, void* ws, size_t ws_bytes, void* stream, uint32_t stages);
+
 /* Gradients of the tensors the score_mod captures (the bias of the ALiBi example, the table of the
  * relative-bias example, section 3.1), which flexattn_backward does not produce:
  *   d_alibi_bias [Hq] fp32          sum over b, q, kv of dS * (q_idx - kv_idx)

@@ -129,6 +129,11 @@ def _lib():
                                       P(_Tensor), P(_Tensor), P(_Tensor), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.flexattn_backward_stages.restype = C.c_int
     lib.flexattn_backward_stages.argtypes = lib.flexattn_backward.argtypes + [C.c_uint32]
+    lib.flexattn_backward_stored_workspace_bytes.restype = C.c_size_t
+    lib.flexattn_backward_stored_workspace_bytes.argtypes = [P(_Dims), P(_BlockMask), C.c_int64]
+    lib.flexattn_backward_stored.restype = C.c_int
+    lib.flexattn_backward_stored.argtypes = (lib.flexattn_backward.argtypes[:15] +
+                                             [C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint32])
     lib.flexattn_backward_captured_workspace_bytes.restype = C.c_size_t
     lib.flexattn_backward_captured_workspace_bytes.argtypes = [P(_Dims), P(_BlockMask), C.c_uint32, P(_ModParams)]
     lib.flexattn_backward_captured.restype = C.c_int
@@ -350,6 +355,30 @@ def flexattn_backward(Q, K, V, O, dO, LSE, score_id: int, mask_id: int, params: 
     _check(_lib().flexattn_backward(C.byref(d), *(C.byref(t) for t in ts[:5]), LSE.data_ptr(), score_id, mask_id,
                                     C.byref(p), C.byref(c), scale, *(C.byref(t) for t in ts[5:]),
                                     ws.data_ptr(), ws.numel(), _stream()), "flexattn_backward")
+    return dQ, dK, dV
+
+
+def flexattn_backward_stored_workspace_bytes(Q, K, bm: BlockMask, n_blocks: int) -> int:
+    d, c = _dims(Q, K), bm._c()
+    return _lib().flexattn_backward_stored_workspace_bytes(C.byref(d), C.byref(c), n_blocks)
+
+
+def flexattn_backward_stored(Q, K, V, O, dO, LSE, score_id: int, mask_id: int, params: ModParams, bm: BlockMask,
+                             scale: float, dQ, dK, dV, n_blocks: int, ws: Optional[torch.Tensor] = None,
+                             stages: int = 7):
+    """The backward that keeps dS in memory; n_blocks = stats[0] + stats[1] of the BlockMask build.
+    dQ / dK / dV may be None for stages that are not selected; `ws` must persist between stages."""
+    if ws is None:
+        n = flexattn_backward_stored_workspace_bytes(Q, K, bm, n_blocks)
+        ws = torch.empty(max(n, 1), dtype=torch.uint8, device=Q.device)
+    d, p, c = _dims(Q, K), params._c(), bm._c()
+    ins = [_tensor(t) for t in (Q, K, V, O, dO)]
+    outs = [None if t is None else _tensor(t) for t in (dQ, dK, dV)]
+    _check(_lib().flexattn_backward_stored(C.byref(d), *(C.byref(t) for t in ins), LSE.data_ptr(), score_id,
+                                           mask_id, C.byref(p), C.byref(c), scale,
+                                           *(None if t is None else C.byref(t) for t in outs),
+                                           n_blocks, ws.data_ptr(), ws.numel(), _stream(), stages),
+           "flexattn_backward_stored")
     return dQ, dK, dV
 
 

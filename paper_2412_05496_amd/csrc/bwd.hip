@@ -1,5 +1,5 @@
 // flexattn_backward: argument validation, the delta pre-pass and dispatch to the compiled variant.
-#include "bwd_kernel.h"
+#include "bwd_stored.h"
 #include "variants.h"
 
 namespace flexattn {
@@ -24,13 +24,41 @@ extern "C" size_t flexattn_backward_workspace_bytes(const flexattn_dims* d) {
     return (size_t)2 * d->B * d->Hq * d->q_len * sizeof(float);
 }
 
-extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexattn_tensor* Q,
+namespace {
+// Workspace of the backward that keeps dS in memory: the row scalars of the recomputing backward,
+// then the slot numbering (column bases, grid), then the dS blocks.
+struct StoredLayout {
+    size_t colbase_off, grid_off, store_off, total;
+    int64_t cap;        // slots per head
+    int lines, planes;
+};
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+bool stored_layout(const flexattn_dims* d, const flexattn_blockmask* bm, int64_t n_blocks, StoredLayout* out) {
+    if (!d || !bm || d->B <= 0 || d->Hq <= 0 || d->q_len <= 0 || d->kv_len <= 0 || n_blocks < 0) return false;
+    if (bm->Bq <= 0 || bm->Bk <= 0 || bm->Bm <= 0 || bm->Hm <= 0) return false;
+    const int64_t NR = (d->q_len + bm->Bq - 1) / bm->Bq, NC = (d->kv_len + bm->Bk - 1) / bm->Bk;
+    const int64_t planes = (int64_t)bm->Bm * bm->Hm, lines = planes * NC;
+    const int64_t cap = n_blocks > 0 ? n_blocks : 1;
+    if (lines >= (1ll << 30) || planes * NR * NC >= (1ll << 40) || cap * (bm->Bk / 64 + 1) >= (1ll << 31)) return false;
+    const int64_t reps = (int64_t)(bm->Bm > 1 ? 1 : d->B) * (bm->Hm > 1 ? 1 : d->Hq);
+    out->cap = cap;
+    out->lines = (int)lines;
+    out->planes = (int)planes;
+    out->colbase_off = align256(flexattn_backward_workspace_bytes(d));
+    out->grid_off = out->colbase_off + align256((size_t)(lines + 1) * sizeof(int32_t));
+    out->store_off = out->grid_off + align256((size_t)(planes * NR * NC) * sizeof(int32_t));
+    out->total = out->store_off + (size_t)reps * (size_t)cap * (size_t)bm->Bq * (size_t)bm->Bk * sizeof(bf16);
+    return true;
+}
+
+// ds_blocks < 0: dQ recomputes S and dP; otherwise dS goes through memory (every stage runs).
+int backward_impl(const flexattn_dims* dims, const flexattn_tensor* Q,
                                         const flexattn_tensor* K, const flexattn_tensor* V, const flexattn_tensor* O,
                                         const flexattn_tensor* dO, const float* LSE, uint32_t score_id,
                                         uint32_t mask_id, const flexattn_mod_params* params,
                                         const flexattn_blockmask* bm, float scale, const flexattn_tensor* dQ,
                                         const flexattn_tensor* dK, const flexattn_tensor* dV, void* ws,
-                                        size_t ws_bytes, void* stream, uint32_t stages) {
+                                        size_t ws_bytes, void* stream, uint32_t stages, int64_t ds_blocks) {
     int rc = check_problem(dims, bm);
     if (rc != FLEXATTN_OK) return rc;
     if (stages == 0 || (stages & ~FLEXATTN_BWD_ALL)) return FLEXATTN_ERR_INVALID_ARG;
@@ -54,7 +82,15 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
     if ((rc = check_canvas(mask_id, params, dims->q_len, dims->kv_len)) != FLEXATTN_OK) return rc;
     const int vi = find_variant(mask_id, score_id);
     if (vi < 0) return FLEXATTN_ERR_UNSUPPORTED;
-    if (ws_bytes < flexattn_backward_workspace_bytes(dims)) return FLEXATTN_ERR_WORKSPACE;
+    const bool stored = ds_blocks >= 0;
+    StoredLayout lay = {};
+    if (stored) {
+        if (!stored_layout(dims, bm, ds_blocks, &lay)) return FLEXATTN_ERR_INVALID_ARG;
+        if (((uintptr_t)ws & 255)) return FLEXATTN_ERR_INVALID_ARG;
+        if (ws_bytes < lay.total) return FLEXATTN_ERR_WORKSPACE;
+    } else if (ws_bytes < flexattn_backward_workspace_bytes(dims)) {
+        return FLEXATTN_ERR_WORKSPACE;
+    }
 
     BwdArgs a = {};
     a.Q = (const bf16*)Q->ptr; a.K = (const bf16*)K->ptr; a.V = (const bf16*)V->ptr;
@@ -62,6 +98,16 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
     a.dQ = (bf16*)dQ->ptr; a.dK = (bf16*)dK->ptr; a.dV = (bf16*)dV->ptr;
     const size_t rows = (size_t)dims->B * dims->Hq * dims->q_len;
     a.delta = (float*)ws; a.lse2 = (float*)ws + rows;
+    int32_t* colbase = nullptr;
+    int32_t* grid = nullptr;
+    if (stored) {
+        colbase = (int32_t*)((char*)ws + lay.colbase_off);
+        grid = (int32_t*)((char*)ws + lay.grid_off);
+        a.ds_colbase = colbase;
+        a.ds_grid = grid;
+        a.ds_store = (bf16*)((char*)ws + lay.store_off);
+        a.ds_blocks = lay.cap;
+    }
     a.q_sb = Q->stride_b; a.q_sh = Q->stride_h; a.q_ss = Q->stride_s;
     a.k_sb = K->stride_b; a.k_sh = K->stride_h; a.k_ss = K->stride_s;
     a.v_sb = V->stride_b; a.v_sh = V->stride_h; a.v_ss = V->stride_s;
@@ -84,12 +130,40 @@ extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexatt
     if (params) a.p = *params;
 
     hipStream_t st = (hipStream_t)stream;
-    const uint32_t delta_stage = stages & FLEXATTN_BWD_DELTA;
-    (void)delta_stage;
-    rc = kBwdLaunchers[vi](a, dims->D, stages, st);     // the delta pre-pass depends on the score_mod too
-    if (rc != FLEXATTN_OK) return rc;
+    if (stored) {
+        if (stages & FLEXATTN_BWD_DELTA) {      // the block numbering belongs to the pre-pass
+            hipLaunchKernelGGL(bwd_slots_scan_kernel, dim3(1), dim3(1024), 0, st, a.q_num, a.full_q_num, lay.lines,
+                               a.NR, colbase);
+            hipLaunchKernelGGL(bwd_slots_fill_kernel, dim3((unsigned)lay.lines), dim3(256), 0, st, a.q_num, a.q_idx,
+                               a.full_q_num, a.full_q_idx, a.NR, a.NC, colbase, grid);
+        }
+        // delta and dK/dV (which writes dS) from the compiled variant; dQ from what it wrote
+        if (stages & (FLEXATTN_BWD_DELTA | FLEXATTN_BWD_DKDV)) {
+            rc = kBwdLaunchers[vi](a, dims->D, stages & (FLEXATTN_BWD_DELTA | FLEXATTN_BWD_DKDV), st);
+            if (rc != FLEXATTN_OK) return rc;
+        }
+        if (stages & FLEXATTN_BWD_DQ) {
+            const float qscale = scale * ((score_id & FLEXATTN_SCORE_SOFTCAP) ? 4.0f : 1.0f);   // ScoreMod::grad_scale()
+            launch_bwd_stored_dq(a, dims->D, qscale, st);
+        }
+    } else {
+        rc = kBwdLaunchers[vi](a, dims->D, stages, st);     // the delta pre-pass depends on the score_mod too
+        if (rc != FLEXATTN_OK) return rc;
+    }
     FLEXATTN_HIP_TRY(hipGetLastError());
     return FLEXATTN_OK;
+}
+}  // namespace
+
+extern "C" int flexattn_backward_stages(const flexattn_dims* dims, const flexattn_tensor* Q,
+                                        const flexattn_tensor* K, const flexattn_tensor* V, const flexattn_tensor* O,
+                                        const flexattn_tensor* dO, const float* LSE, uint32_t score_id,
+                                        uint32_t mask_id, const flexattn_mod_params* params,
+                                        const flexattn_blockmask* bm, float scale, const flexattn_tensor* dQ,
+                                        const flexattn_tensor* dK, const flexattn_tensor* dV, void* ws,
+                                        size_t ws_bytes, void* stream, uint32_t stages) {
+    return backward_impl(dims, Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, scale, dQ, dK, dV, ws, ws_bytes,
+                         stream, stages, -1);
 }
 
 extern "C" int flexattn_backward(const flexattn_dims* dims, const flexattn_tensor* Q, const flexattn_tensor* K,
@@ -100,6 +174,23 @@ extern "C" int flexattn_backward(const flexattn_dims* dims, const flexattn_tenso
                                  void* ws, size_t ws_bytes, void* stream) {
     return flexattn_backward_stages(dims, Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, scale, dQ, dK, dV, ws,
                                     ws_bytes, stream, FLEXATTN_BWD_ALL);
+}
+
+extern "C" size_t flexattn_backward_stored_workspace_bytes(const flexattn_dims* dims, const flexattn_blockmask* bm,
+                                                           int64_t n_blocks) {
+    StoredLayout lay;
+    return stored_layout(dims, bm, n_blocks, &lay) ? lay.total : 0;
+}
+
+extern "C" int flexattn_backward_stored(const flexattn_dims* dims, const flexattn_tensor* Q, const flexattn_tensor* K,
+                                        const flexattn_tensor* V, const flexattn_tensor* O, const flexattn_tensor* dO,
+                                        const float* LSE, uint32_t score_id, uint32_t mask_id,
+                                        const flexattn_mod_params* params, const flexattn_blockmask* bm, float scale,
+                                        const flexattn_tensor* dQ, const flexattn_tensor* dK, const flexattn_tensor* dV,
+                                        int64_t n_blocks, void* ws, size_t ws_bytes, void* stream, uint32_t stages) {
+    if (n_blocks < 0) return FLEXATTN_ERR_INVALID_ARG;
+    return backward_impl(dims, Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, scale, dQ, dK, dV, ws, ws_bytes,
+                         stream, stages, n_blocks);
 }
 
 // ---- gradients of captured tensors -----------------------------------------------------------

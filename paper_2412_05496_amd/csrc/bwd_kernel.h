@@ -55,9 +55,32 @@ struct BwdArgs {
     const int32_t* full_q_idx;
     const int32_t* kv_order;   // nullable work orders (rows / columns of blocks, longest first)
     const int32_t* q_order;
+    // dS kept in memory (bwd_stored.h): the dK/dV kernel writes the dS of every block it visits, a lean
+    // kernel contracts it with K.  Null ds_store: nothing is written.
+    bf16* ds_store;            // [heads that share no dS, ds_blocks, Bk / 64, Bq / 64, 4096] (see ds_chunk)
+    const int32_t* ds_colbase; // [planes * NC] first block slot of every column of blocks
+    const int32_t* ds_grid;    // [planes, NR, NC] slot of block (row, column)
+    int64_t ds_blocks;         // slots per head (capacity)
     float scale;
     flexattn_mod_params p;
 };
+
+// dS in memory.  The non-empty blocks of all BlockMask planes are numbered column by column of blocks,
+// in the order of the merged (FULL, then PARTIAL) column lists: that number is the block's slot.
+// Heads that share a plane share the numbering and differ in `rep`.  A block is cut into Bk / 64 tiles
+// of 64 keys, a tile into Bq / 64 steps of 64 query rows, and a step is the 8 KiB the four waves of
+// the dK/dV workgroup hold in registers after the step: wave (kb, x) two chunks of 1 KiB, lane
+// (key 32 kb + l32, half h) 16 bytes of each -- chunk c holds rows 32 x + 16 c + 8 jj + 4 h + i at
+// position 4 jj + i.  Slots are clamped to the capacity: a caller that passes too small a capacity
+// gets wrong gradients, never an access outside the workspace.
+__device__ __forceinline__ int64_t ds_rep(const BwdArgs& a, int b, int hq) {
+    return (int64_t)(a.bm_Bm > 1 ? 0 : b) * (a.bm_Hm > 1 ? 1 : a.Hq) + (a.bm_Hm > 1 ? 0 : hq);
+}
+// index of the 8 KiB step (in units of 4096 bf16) of block `slot`, key tile `st`, row step `sidx`
+__device__ __forceinline__ int64_t ds_chunk(const BwdArgs& a, int64_t rep, int slot, int st, int sidx) {
+    const int64_t sl = min(max((int64_t)slot, (int64_t)0), a.ds_blocks - 1);
+    return ((rep * a.ds_blocks + sl) * (a.Bk / 64) + st) * (a.Bq / 64) + sidx;
+}
 
 // ------------------------------------------------------------------------------------------
 // -delta = -rowsum(dO * O) and the per-row constant rc of ScoreMod::p_with_grad (so that the main
@@ -139,7 +162,8 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
         const int64_t plane0 = (int64_t)(a.bm_Bm > 1 ? b : 0) * a.bm_Hm + (a.bm_Hm > 1 ? hkv * a.G : 0);
         col = min(max(a.q_order[plane0 * a.NC + col], 0), a.NC - 1);   // clamped: a bad order array stays inside the lists
     }
-    const int tile = col * sub_k + slot % sub_k;
+    const int key_tile = slot % sub_k;             // which 64 keys of the column of blocks
+    const int tile = col * sub_k + key_tile;
     const int kv0 = tile * 64;
     if (kv0 >= a.kv_len) return;
 
@@ -185,6 +209,7 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
     const uint32_t row_lds = lds_addr(&s_row[0][0][0]) + (32 * x + 4 * half) * 4;
     const uint32_t xchg_mine = lds_addr(&s_xchg[w][0][lane]), xchg_theirs = lds_addr(&s_xchg[w ^ 2][0][lane]);
     const int q_off = q_offset_of(a.p, b);
+    const int ds_lane = w * 1024 + lane * 8;     // this lane's place inside a step of dS in memory (bf16 elements)
 
     for (int g = 0; g < a.G; ++g) {
         const int hq = hkv * a.G + g;
@@ -194,6 +219,9 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
         const int32_t* part_idx = a.q_idx + line * a.NR;
         const int H_all = (n_full + n_part) * sub;  // steps
         if (H_all == 0) continue;
+        // dS to memory: slot of this column's first block, and which copy of the numbering hq writes
+        const int ds_slot0 = a.ds_store ? ldc(a.ds_colbase + line) : 0;
+        const int64_t ds_head = a.ds_store ? ds_rep(a, b, hq) : 0;
         const i32x4 q_rsrc = make_rsrc(a.Q + b * a.q_sb + hq * a.q_sh, q_bytes);
         const i32x4 do_rsrc = make_rsrc(a.dO + b * a.do_sb + hq * a.do_sh, do_bytes);
         // waves 0, 2 fetch the rc row, waves 1, 3 the -delta row (the duplicates write the same values)
@@ -222,6 +250,7 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
             }
             __syncthreads();
             int ld_v = 0;                           // step whose loads are issued next
+            int u_step = H_all - 1 - seg0;          // position of the current step in the column's walk (counts down)
             int e_next = s_steps[0];
             int q0_of[2];                           // first query row of the step in each ring slot,
             bool part_of[2];                        // and whether its block is PARTIAL
@@ -347,6 +376,14 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
                         dsk[e >> 2][e & 3] = pack_bf16(ds[2 * i], ds[2 * i + 1]);
                     }
                 }
+                if (a.ds_store) {       // (wave-uniform) this wave's dS of the step, as it sits in the registers
+                    const int u = u_step, pos = u / sub;
+                    bf16* dst = a.ds_store + ds_chunk(a, ds_head, ds_slot0 + pos, key_tile, u - pos * sub) * 4096 + ds_lane;
+                    // (written once, read once by another kernel much later: no reason to keep it in a cache)
+                    __builtin_nontemporal_store(dsk[0], (u32x4*)dst);
+                    __builtin_nontemporal_store(dsk[1], (u32x4*)(dst + 512));
+                }
+                --u_step;
                 // exchange: keep what this wave's output needs, hand over the other
                 u32x4 own[2];
 #pragma unroll
@@ -377,7 +414,10 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
                 for (int c = 0; c < 2; ++c)
                     theirs[c] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(xchg_theirs + c * 1024);
                 out_half(tr_other, theirs);
-                wait_vmem();
+                // the next step's tiles must have landed; the two dS stores, the youngest vector-memory
+                // operations of the step (the counter retires in issue order), may still be under way
+                if (a.ds_store) wait_vmem_but<2>();
+                else wait_vmem();
                 __syncthreads();
             };
 

@@ -33,6 +33,13 @@ __device__ __forceinline__ constexpr int tile_off(int row, int chunk) {
 
 // vmcnt(0): every global load (including loads into LDS) this wave issued has completed.
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// vmcnt(N): all but the N most recently issued vector-memory operations of this wave have completed
+// (loads, LDS-DMA loads and stores retire from the counter in the order they were issued).
+template <int N>
+__device__ __forceinline__ void wait_vmem_but() {
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 // Raw buffer resource (four scalar dwords) over `bytes` bytes at `p`: no stride, loads beyond
 // the end return zero instead of faulting.
@@ -93,6 +100,12 @@ __device__ __forceinline__ void dma_global(uint32_t lds, const void* gptr) {
 
 __device__ __forceinline__ void dma_x1(i32x4 rsrc, uint32_t lds, int v0, int soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(v0), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
+}
+
+// The same with the non-temporal hint, for data that is read exactly once.
+__device__ __forceinline__ void dma_x1_nt(i32x4 rsrc, uint32_t lds, int v0, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
                  :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(v0), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 

@@ -99,14 +99,25 @@ def run_forward(wl, inp, dev, Hm=1):
     return O, LSE, bm, (mask_id, score_id, params, Q, K, V)
 
 
-def run_backward(wl, inp, dev, O, LSE, bm, ids):
+def nonempty_blocks(bm):
+    """PARTIAL + FULL blocks of all planes: the capacity the backward that keeps dS in memory asks for."""
+    st = bm.stats.cpu().tolist()
+    return int(st[0] + st[1])
+
+
+def run_backward(wl, inp, dev, O, LSE, bm, ids, stored=False):
+    """stored: through flexattn_backward_stored (dS kept in memory) instead of flexattn_backward."""
     import paper_2412_05496_amd as fa
     mask_id, score_id, params, Q, K, V = ids
     dO = inp.dO.to(dev)
     dQ = torch.full_like(Q, float("nan"))
     dK = torch.full_like(K, float("nan"))
     dV = torch.full_like(V, float("nan"))
-    fa.flexattn_backward(Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV)
+    if stored:
+        fa.flexattn_backward_stored(Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV,
+                                    nonempty_blocks(bm))
+    else:
+        fa.flexattn_backward(Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV)
     torch.cuda.synchronize()
     return dQ, dK, dV
 

@@ -33,7 +33,12 @@ def check_full_size(wl, heads, n_rows, col_groups):
     print(f"[case] {wl.name}: forward + backward on the GPU", flush=True)
     O, LSE, bm, ids = run_forward(wl, inp, DEV)
     dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids)
-    O, LSE, dQ, dK, dV = (t.cpu() for t in (O, LSE, dQ, dK, dV))
+    # the backward that keeps dS in memory: dK / dV come from the same kernel (same bits), its dQ is
+    # checked on the sampled rows like the other one
+    dQ_st, dK_st, dV_st = run_backward(wl, inp, DEV, O, LSE, bm, ids, stored=True)
+    assert torch.equal(dK_st, dK) and torch.equal(dV_st, dV)
+    del dK_st, dV_st
+    O, LSE, dQ, dK, dV, dQ_st = (t.cpu() for t in (O, LSE, dQ, dK, dV, dQ_st))
     G = wl.Hq // wl.Hkv
     gen = torch.Generator().manual_seed(wl.seed + 7)
     for (b, h) in heads:
@@ -45,6 +50,7 @@ def check_full_size(wl, heads, n_rows, col_groups):
         check_output(O[b, h, rows], LSE[b, h, rows], o_ref, l_ref)
         dq_ref, _, _ = fo.attention_head_backward(*args, inp.dO[b, h], score, mask, inp.scale, b, h, q_rows=rows)
         check_grad("dQ", dQ[b, h, rows], dq_ref)
+        check_grad("dQ (dS kept in memory)", dQ_st[b, h, rows], dq_ref)
     for (b, hkv, cols) in col_groups:
         dk_ref = torch.zeros(cols.numel(), wl.D, dtype=torch.float64)
         dv_ref = torch.zeros_like(dk_ref)
