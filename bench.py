@@ -61,9 +61,11 @@ def event_time_ms(fn, iters: int) -> float:
     return start.elapsed_time(stop) / iters
 
 
-def train_leg(fa, wlm, wl, dev, iters: int, mfma_tflops: float) -> dict:
+def train_leg(fa, wlm, wl, dev, iters: int, mfma_tflops: float, stored: bool = True, time_other: bool = True) -> dict:
     """Forward and backward of one of the other training workloads: ms, TFLOP/s over unmasked FLOPs,
-    fractions of the datasheet and of the measured MFMA rate, BlockMask density."""
+    fractions of the datasheet and of the measured MFMA rate, BlockMask density.  `stored`: the backward
+    is flexattn_backward_stored (dS kept in memory) rather than flexattn_backward; `time_other`: the
+    other one is timed beside it."""
     import torch
     inp = wlm.make_train_inputs(wl, with_dO=True)
     Q, Kt, V, dO = (t.to(dev) for t in (inp.Q, inp.K, inp.V, inp.dO))
@@ -78,33 +80,33 @@ def train_leg(fa, wlm, wl, dev, iters: int, mfma_tflops: float) -> dict:
         params = fa.ModParams(window=wl.window, prefix_len=wl.prefix_len, rel_bias=inp.rel_bias.to(dev))
     bm = fa.alloc_blockmask(Bm, 1, wl.S, wl.S, wl.Bq, wl.Bk, device=dev)
     fa.flexattn_blockmask_build(mask_id, params, bm)
+    partial, full, total, unmasked = bm.stats.cpu().tolist()
+    pairs = unmasked * (wl.B // Bm) * wl.Hq
     O = torch.empty_like(Q)
     LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=dev)
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Kt), torch.empty_like(V)
     ws = torch.empty(fa.flexattn_backward_workspace_bytes(Q, Kt), dtype=torch.uint8, device=dev)
     fwd = lambda: fa.flexattn_forward(Q, Kt, V, score_id, mask_id, params, bm, inp.scale, O, LSE)
-    bwd = lambda st=fa.BWD_ALL: fa.flexattn_backward_stages(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm,
-                                                            inp.scale, dQ, dK, dV, ws, st)
+    bwd_rc = lambda st=fa.BWD_ALL: fa.flexattn_backward_stages(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm,
+                                                               inp.scale, dQ, dK, dV, ws, st)
+    st_ws = None
+    if stored or time_other:
+        st_ws = torch.empty(fa.flexattn_backward_stored_workspace_bytes(Q, Kt, bm, partial + full), dtype=torch.uint8,
+                            device=dev)
+    bwd_st = lambda st=fa.BWD_ALL: fa.flexattn_backward_stored(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm,
+                                                               inp.scale, dQ, dK, dV, partial + full, st_ws, st)
+    bwd, bwd_other = (bwd_st, bwd_rc) if stored else (bwd_rc, bwd_st)
     fwd(), bwd()
     torch.cuda.synchronize()
     t_f, t_b = event_time_ms(fwd, iters), event_time_ms(bwd, iters)
     t_dkdv = event_time_ms(lambda: bwd(fa.BWD_DKDV), iters)
     t_dq = event_time_ms(lambda: bwd(fa.BWD_DQ), iters)
-    partial, full, total, unmasked = bm.stats.cpu().tolist()
-    pairs = unmasked * (wl.B // Bm) * wl.Hq
-    # the backward that keeps dS in memory, for comparison (it pays where the head dimension is large
-    # and the score_mod costly; the figures of this leg are those of the recomputing backward)
-    st_ws = torch.empty(fa.flexattn_backward_stored_workspace_bytes(Q, Kt, bm, partial + full), dtype=torch.uint8,
-                        device=dev)
-    bwd_st = lambda: fa.flexattn_backward_stored(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale,
-                                                 dQ, dK, dV, partial + full, st_ws)
-    bwd_st()
-    t_st = event_time_ms(bwd_st, iters)
     f_f, f_b = 4 * wl.D * pairs / (t_f * 1e-3) / 1e12, 10 * wl.D * pairs / (t_b * 1e-3) / 1e12
     leg = {
-        "workload": wl.name, "pairs": pairs, "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4),
-        "bwd_dkdv_ms": round(t_dkdv, 4), "bwd_dq_ms": round(t_dq, 4),
-        "bwd_with_dS_in_memory_ms": round(t_st, 4), "bwd_with_dS_in_memory_workspace_gb": round(st_ws.numel() / 1e9, 2),
+        "workload": wl.name, "pairs": pairs, "fwd_ms": round(t_f, 4),
+        "bwd": "flexattn_backward_stored (dS kept in memory)" if stored else "flexattn_backward (dQ recomputes S, dP)",
+        "bwd_ms": round(t_b, 4), "bwd_dkdv_ms": round(t_dkdv, 4), "bwd_dq_ms": round(t_dq, 4),
+        "bwd_workspace_gb": round((st_ws if stored else ws).numel() / 1e9, 3),
         "fwd_tflops": round(f_f, 1), "bwd_tflops": round(f_b, 1),
         "fwd_frac_of_bf16_peak": round(f_f / PEAK_BF16_TFLOPS, 4),
         "bwd_frac_of_bf16_peak": round(f_b / PEAK_BF16_TFLOPS, 4),
@@ -115,6 +117,9 @@ def train_leg(fa, wlm, wl, dev, iters: int, mfma_tflops: float) -> dict:
                       "element_density": round(unmasked / (Bm * wl.S * wl.S), 4),
                       "executed_over_unmasked_pairs": round((partial + full) * wl.Bq * wl.Bk / unmasked, 4)},
     }
+    if time_other:
+        bwd_other()
+        leg["bwd_recompute_ms" if stored else "bwd_stored_ms"] = round(event_time_ms(bwd_other, iters), 4)
     if note:
         leg["note"] = note
     return leg
@@ -128,6 +133,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the cfg3 / cfg4 legs")
+    ap.add_argument("--bwd-path", choices=("stored", "recompute"), default="stored",
+                    help="the backward of the timed step: flexattn_backward_stored (dS kept in memory, default) or "
+                         "flexattn_backward (S and dP recomputed for dQ)")
+    ap.add_argument("--one-bwd-path", action="store_true",
+                    help="do not time the other backward beside the step's (for profiler runs: both use the same dK/dV kernel)")
     ap.add_argument("--cpu-heads", type=int, default=12, help="(b, h) slices the oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for HBM byte counters)")
@@ -183,9 +193,12 @@ def main() -> int:
         fa.flexattn_backward_stages(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV,
                                     bwd_ws, stages)
 
-    def bwd(stages=fa.BWD_ALL):
+    def bwd_stored(stages=fa.BWD_ALL):
         fa.flexattn_backward_stored(Q, Kt, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV,
                                     n_blocks, st_ws, stages)
+
+    stored = args.bwd_path == "stored"
+    bwd, bwd_other = (bwd_stored, bwd_recompute) if stored else (bwd_recompute, bwd_stored)
 
     def step():
         build()
@@ -217,19 +230,18 @@ def main() -> int:
         "bwd_dq": event_time_ms(lambda: bwd(fa.BWD_DQ), K),
     }
     # algorithmic FLOPs per launch: forward 4*D*pairs; of the backward's 10*D*pairs (five GEMMs) the
-    # dK/dV kernel executes four GEMMs and the dQ kernel one -- nothing is computed twice
-    alg = {"fwd": flops_fwd, "bwd_dkdv": flops_bwd * 4 / 5, "bwd_dq": flops_bwd * 1 / 5}
+    # dK/dV kernel executes four GEMMs and, with dS in memory, the dQ kernel one -- nothing is computed
+    # twice; the recomputing dQ kernel executes three, and the 10*D*pairs are then split 4 : 3
+    # (recomputation earns nothing)
+    share = (4 / 5, 1 / 5) if stored else (4 / 7, 3 / 7)
+    alg = {"fwd": flops_fwd, "bwd_dkdv": flops_bwd * share[0], "bwd_dq": flops_bwd * share[1]}
     dom = max(alg, key=lambda k: kt[k])
     achieved = alg[dom] / (kt[dom] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(dom),
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": measured_traffic(dom + ("_stored" if stored and dom != "fwd" else "")),
                 "avg_ms": round(kt[dom], 4)}
     bwd_ms = kt["bwd_delta"] + kt["bwd_dkdv"] + kt["bwd_dq"]
-    # the recomputing backward (flexattn_backward): no extra workspace, S and dP computed in both kernels
-    kr = {"bwd_delta": event_time_ms(lambda: bwd_recompute(fa.BWD_DELTA), K),
-          "bwd_dkdv": event_time_ms(lambda: bwd_recompute(fa.BWD_DKDV), K),
-          "bwd_dq": event_time_ms(lambda: bwd_recompute(fa.BWD_DQ), K)}
-    bwd_rec_ms = sum(kr.values())
     out = {
         "metric": "flex_attention fwd+bwd TFLOP/s (unmasked FLOPs), dense causal + softcap",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -237,20 +249,31 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "H": wl.Hq, "S": wl.S, "D": wl.D, "mask": "causal",
                    "score_mod": "tanh softcap 30", "block": f"{wl.Bq}x{wl.Bk}",
-                   "step": "blockmask_build + forward + backward (dS kept in memory)"},
+                   "step": "blockmask_build + forward + backward "
+                           + ("(flexattn_backward_stored: dS kept in memory)" if stored else "(flexattn_backward: dQ recomputes S, dP)")},
         "fwd_tflops": round(flops_fwd / (kt["fwd"] * 1e-3) / 1e12, 2),
         "fwd_frac_of_bf16_peak": round(flops_fwd / (kt["fwd"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "bwd_tflops": round(flops_bwd / (bwd_ms * 1e-3) / 1e12, 2),
         "bwd_frac_of_bf16_peak": round(flops_bwd / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "kernel_ms": {k: round(v, 4) for k, v in kt.items()},
-        "bwd_workspace_gb": round(st_ws.numel() / 1e9, 2),
-        "bwd_recompute": {"what": "flexattn_backward: dQ recomputes S and dP (7 GEMMs for the 5 credited), 4 MB workspace",
-                          "kernel_ms": {k: round(v, 4) for k, v in kr.items()}, "bwd_ms": round(bwd_rec_ms, 4),
-                          "bwd_tflops": round(flops_bwd / (bwd_rec_ms * 1e-3) / 1e12, 2),
-                          "bwd_frac_of_bf16_peak": round(flops_bwd / (bwd_rec_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+        "bwd_workspace_gb": round((st_ws if stored else bwd_ws).numel() / 1e9, 3),
         "blockmask": {"partial": stats[0], "full": stats[1], "total": stats[2]},
         "roofline": roofline,
     }
+
+    if not args.one_bwd_path:
+        # the library's other backward on the same inputs
+        bwd_other()
+        ko = {"bwd_delta": event_time_ms(lambda: bwd_other(fa.BWD_DELTA), K),
+              "bwd_dkdv": event_time_ms(lambda: bwd_other(fa.BWD_DKDV), K),
+              "bwd_dq": event_time_ms(lambda: bwd_other(fa.BWD_DQ), K)}
+        other_ms = sum(ko.values())
+        out["bwd_recompute" if stored else "bwd_stored"] = {
+            "what": ("flexattn_backward: dQ recomputes S and dP (7 GEMMs for the 5 credited), 4 MB workspace" if stored
+                     else "flexattn_backward_stored: dS written by dK/dV and read by dQ (5 GEMMs), 4.4 GB workspace"),
+            "kernel_ms": {k: round(v, 4) for k, v in ko.items()}, "bwd_ms": round(other_ms, 4),
+            "bwd_tflops": round(flops_bwd / (other_ms * 1e-3) / 1e12, 2),
+            "bwd_frac_of_bf16_peak": round(flops_bwd / (other_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
 
     # ------------------------------------------------------------------ what the chip sustains
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
@@ -285,7 +308,7 @@ def main() -> int:
         "mfma_with_softcap_bwd_valu_mix_core_ghz": round(ghz_bwd_mix, 3),
         # the two MFMA kernels against the stall-free instruction streams of their hot loops
         "fwd_frac_of_stall_free_mix": round(out["fwd_tflops"] / mix_random, 4),
-        "bwd_dkdv_frac_of_stall_free_mix": round(alg["bwd_dkdv"] / (kt["bwd_dkdv"] * 1e-3) / 1e12 / bwd_mix_random, 4),
+        "bwd_dkdv_frac_of_stall_free_mix": round(8 * wl.D * pairs / (kt["bwd_dkdv"] * 1e-3) / 1e12 / bwd_mix_random, 4),   # the four GEMMs it executes
         "stream_read_gbs": round(read_gbs, 1),
         "how": "flexattn_probe_mfma: nothing but 32x32x16 bf16 MFMAs on register operands, 2 waves per SIMD, "
                "operands of random sign / exponent / mantissa (the chip clocks lower the more the operands toggle: "
@@ -319,7 +342,7 @@ def main() -> int:
     if not args.no_other_configs:
         del Q, Kt, V, dO, O, LSE, dQ, dK, dV
         for key, owl in (("cfg3", wlm.CFG3), ("cfg4", wlm.CFG4)):
-            out[key] = train_leg(fa, wlm, owl, dev, max(3, K // 4), mfma_tflops)
+            out[key] = train_leg(fa, wlm, owl, dev, max(3, K // 4), mfma_tflops, stored, not args.one_bwd_path)
 
     # ------------------------------------------------------------------ paged decode
     if not args.no_decode:

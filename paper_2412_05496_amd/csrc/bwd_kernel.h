@@ -193,7 +193,8 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
 
-    const int sub = a.Bq / TQ;          // steps per BlockMask row block
+    const int sub = a.Bq / TQ;          // steps per BlockMask row block (1 or 2)
+    const int sub_shift = sub >> 1;
     const Loader q_loader(a.q_ss, w, lane), do_loader(a.do_ss, w, lane);
     const uint32_t ring = lds_addr(smem);
     const uint32_t wave_row = lds_addr(&s_row[0][w & 1][0]);
@@ -219,9 +220,16 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
         const int32_t* part_idx = a.q_idx + line * a.NR;
         const int H_all = (n_full + n_part) * sub;  // steps
         if (H_all == 0) continue;
-        // dS to memory: slot of this column's first block, and which copy of the numbering hq writes
-        const int ds_slot0 = a.ds_store ? ldc(a.ds_colbase + line) : 0;
-        const int64_t ds_head = a.ds_store ? ds_rep(a, b, hq) : 0;
+        // dS to memory: where step u of this column's walk goes is ds_col + (pos * sub_k * sub + sidx) * 4096
+        // for u = pos * sub + sidx (everything that does not change with u folded into ds_col, so that a
+        // step pays a handful of scalar instructions); pos is clamped to the capacity
+        bf16* ds_col = nullptr;
+        int ds_pos_max = 0;
+        if (a.ds_store) {
+            const int slot0 = min(max(ldc(a.ds_colbase + line), 0), (int)a.ds_blocks - 1);
+            ds_col = a.ds_store + ds_chunk(a, ds_rep(a, b, hq), slot0, key_tile, 0) * 4096 + ds_lane;
+            ds_pos_max = (int)a.ds_blocks - 1 - slot0;
+        }
         const i32x4 q_rsrc = make_rsrc(a.Q + b * a.q_sb + hq * a.q_sh, q_bytes);
         const i32x4 do_rsrc = make_rsrc(a.dO + b * a.do_sb + hq * a.do_sh, do_bytes);
         // waves 0, 2 fetch the rc row, waves 1, 3 the -delta row (the duplicates write the same values)
@@ -377,8 +385,8 @@ __global__ __launch_bounds__(256, (bwd_waves_per_simd<D, MASK>())) void bwd_dkdv
                     }
                 }
                 if (a.ds_store) {       // (wave-uniform) this wave's dS of the step, as it sits in the registers
-                    const int u = u_step, pos = u / sub;
-                    bf16* dst = a.ds_store + ds_chunk(a, ds_head, ds_slot0 + pos, key_tile, u - pos * sub) * 4096 + ds_lane;
+                    const int u = u_step, pos = u >> sub_shift;
+                    bf16* dst = ds_col + (int64_t)(min(pos, ds_pos_max) * (sub_k * sub) + (u - (pos << sub_shift))) * 4096;
                     // (written once, read once by another kernel much later: no reason to keep it in a cache)
                     __builtin_nontemporal_store(dsk[0], (u32x4*)dst);
                     __builtin_nontemporal_store(dsk[1], (u32x4*)(dst + 512));
