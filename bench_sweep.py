@@ -49,6 +49,17 @@ def library_mods(fa, wl, inp, dev):
     return mask_id, score_id, params, (wl.B if wl.mask == "doc_causal" else 1)
 
 
+def stored_backward_ms(fa, args, n_blocks, iters):
+    """The same backward through flexattn_backward_stored (dS kept in memory); args as for flexattn_backward,
+    n_blocks = PARTIAL + FULL blocks of the BlockMask."""
+    import torch
+    Q, K, bm = args[0], args[1], args[9]
+    ws = torch.empty(fa.flexattn_backward_stored_workspace_bytes(Q, K, bm, n_blocks), dtype=torch.uint8, device=Q.device)
+    t = event_ms(lambda: fa.flexattn_backward_stored(*args, n_blocks, ws), iters)
+    del ws
+    return t
+
+
 def train_point(fa, wlm, wl, iters, tag, dev, force_partial=False):
     import torch
     inp = wlm.make_train_inputs(wl, with_dO=True)
@@ -69,15 +80,18 @@ def train_point(fa, wlm, wl, iters, tag, dev, force_partial=False):
     bwd = lambda: fa.flexattn_backward_stages(Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK,
                                               dV, ws, fa.BWD_ALL)
     t_f, t_b = event_ms(fwd, iters), event_ms(bwd, iters)
+    t_s = stored_backward_ms(fa, (Q, K, V, O, dO, LSE, score_id, mask_id, params, bm, inp.scale, dQ, dK, dV),
+                            int(stats[0] + stats[1]), iters)
     blocks = (wl.S // wl.Bq) * (wl.S // wl.Bk) * Bm
     print(json.dumps({
         "part": tag, "mask": wl.mask, "score": wl.score, "B": wl.B, "Hq": wl.Hq, "Hkv": wl.Hkv, "S": wl.S, "D": wl.D,
         "block": f"{wl.Bq}x{wl.Bk}", "all_partial": force_partial, "pairs": pairs,
         "density": round(pairs / (wl.B * wl.Hq * wl.S * wl.S), 4),
         "blocks_partial_full_total": [stats[0], stats[1], blocks],
-        "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4),
+        "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4), "bwd_stored_ms": round(t_s, 4),
         "fwd_tflops": round(4 * wl.D * pairs / (t_f * 1e-3) / 1e12, 1),
-        "bwd_tflops": round(10 * wl.D * pairs / (t_b * 1e-3) / 1e12, 1)}), flush=True)
+        "bwd_tflops": round(10 * wl.D * pairs / (t_b * 1e-3) / 1e12, 1),
+        "bwd_stored_tflops": round(10 * wl.D * pairs / (t_s * 1e-3) / 1e12, 1)}), flush=True)
 
 
 def decode_point(fa, wlm, wl, iters, tag, dev, identity_table=False):
@@ -163,11 +177,14 @@ def na_point(fa, wlm, canvas, kernel, layout, tile, iters, dev):
     bwd = lambda: fa.flexattn_backward_stages(Q, K, V, O, dO, LSE, fa.SCORE_IDENTITY, fa.MASK_NEIGHBORHOOD, params, bm,
                                               inp.scale, dQ, dK, dV, ws, fa.BWD_ALL)
     t_f, t_b = event_ms(fwd, iters), event_ms(bwd, iters)
+    t_s = stored_backward_ms(fa, (Q, K, V, O, dO, LSE, fa.SCORE_IDENTITY, fa.MASK_NEIGHBORHOOD, params, bm, inp.scale,
+                                  dQ, dK, dV), int(stats[0] + stats[1]), iters)
     print(json.dumps({
         "part": "na", "canvas": canvas, "kernel": kernel, "layout": layout, "tile": tile, "tokens": S,
         "mask_density": round(stats[3] / (S * S), 5),
         "block_density": round((stats[0] + stats[1]) / stats[2], 5),
         "blocks_partial_full_total": stats[:3], "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4),
+        "bwd_stored_ms": round(t_s, 4),
         "fwd_tflops": round(4 * wl.D * pairs / (t_f * 1e-3) / 1e12, 1),
         "bwd_tflops": round(10 * wl.D * pairs / (t_b * 1e-3) / 1e12, 1)}), flush=True)
 

@@ -274,6 +274,10 @@ int flexattn_backward_stages(const flexattn_dims* dims,
  * The dK/dV kernel writes the gradient of the scores of every non-empty block it visits (section
  * 4.2's transposed walk) and dQ = scale * dS K is then one block-sparse product over the written
  * blocks: the backward executes the five matrix products of its definition instead of seven.
+ * Whether it pays depends on what the recomputation costs against 4 bytes of HBM traffic per
+ * unmasked score: measured on MI355X it is 9-12 % faster at D = 128 (soft-cap or relative bias),
+ * 23-25 % faster for masks whose blocks are mostly PARTIAL (neighborhood attention, D = 64), even
+ * at D = 64 with a soft-cap, and 15-25 % slower at D = 64 with a plain score_mod.
  *   n_blocks  capacity, in blocks of Bq x Bk scores: at least the number of non-empty (PARTIAL +
  *             FULL) blocks of the BlockMask, all planes together -- stats[0] + stats[1] of
  *             flexattn_blockmask_build.  A smaller value gives wrong gradients for the blocks that
