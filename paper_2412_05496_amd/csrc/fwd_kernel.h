@@ -248,7 +248,12 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
             mx = fmaxf(mx, swap_halves(mx));
             if constexpr (kScaleOnly) mx *= smod.k_acc;
-            const float m_new = fmaxf(m_run, mx);
+            // The running maximum only has to keep exp2(s - m) in range, so it follows the scores lazily:
+            // a row keeps its old maximum until a block exceeds it by more than kLazyMax (P then reaches
+            // 2^kLazyMax at most, the row sum as much more; O / l and LSE = m + log2 l come out the same).
+            // On most blocks no row of the wave moves its maximum, and the rescaling of O^T is skipped.
+            constexpr float kLazyMax = 8.0f;
+            const float m_new = mx > m_run + kLazyMax ? mx : m_run;
             const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
             const float alpha = fast_exp2(m_run - m_use);
             m_run = m_new;
