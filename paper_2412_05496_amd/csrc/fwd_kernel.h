@@ -189,6 +189,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
     // base-2 running max and this lane's part of the running sum; with a bounded soft-cap the
     // maximum is fixed at the cap from the start
     float m_run = BOUNDED ? smod.capl2 : -INFINITY, l_run = 0.0f;
+    float m_use = 0.0f;     // the maximum the exponentials subtract: m_run, or 0 while the row has seen no key
 
     // score_mod, mask_mod (partial blocks only) and softmax of one 32-key block whose first key is
     // kvs: s -> P^T as two bf16 fragments.  The mask is a separate, rarely taken pass (kept a real
@@ -253,20 +254,21 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
             // 2^kLazyMax at most, the row sum as much more; O / l and LSE = m + log2 l come out the same).
             // On most blocks no row of the wave moves its maximum, and the rescaling of O^T is skipped.
             constexpr float kLazyMax = 8.0f;
-            const float m_new = mx > m_run + kLazyMax ? mx : m_run;
-            const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-            const float alpha = fast_exp2(m_run - m_use);
-            m_run = m_new;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                s[r] = fast_exp2(kScaleOnly ? __builtin_fmaf(s[r], smod.k_acc, -m_use) : s[r] - m_use);
-            l_run *= alpha;
-            if (__any(alpha != 1.0f)) {
+            if (__any(mx > m_run + kLazyMax)) {      // some row of the wave moves its maximum
+                const float m_new = mx > m_run + kLazyMax ? mx : m_run;
+                const float m_new_use = (m_new == -INFINITY) ? 0.0f : m_new;
+                const float alpha = fast_exp2(m_run - m_new_use);   // 1 for the rows that stay, 0 for a row's first keys
+                m_run = m_new;
+                m_use = m_new_use;
+                l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
             }
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                s[r] = fast_exp2(kScaleOnly ? __builtin_fmaf(s[r], smod.k_acc, -m_use) : s[r] - m_use);
         }
         // The row sum adds up the bf16-rounded probabilities, the values P V is computed from, two at
         // a time (dot product of a packed pair with (1, 1), fp32 accumulation).
