@@ -364,6 +364,29 @@ struct ScoreMod {
         }
     }
 
+    // apply() + shift with the addition folded into the multiply-adds that are there anyway (the
+    // online softmax passes minus its running maximum: the score arrives ready for exp2).
+    template <bool UNI = false>
+    __device__ __forceinline__ float apply_shifted(float acc, RelPos rp, float uni, float shift) const {
+        if constexpr (kCap) {
+            return __builtin_fmaf(-2.0f * capl2, cap_r<UNI>(acc, rp, uni), capl2 + shift);
+        } else if constexpr (kAlibi) {
+            float y = __builtin_fmaf(acc, k_acc, __builtin_fmaf(k_bias, rp.c, rp.abase + ((kRel && UNI) ? uni + shift : shift)));
+            if constexpr (kRel && !UNI) y += rel_entry(rp.dq);
+            return y;
+        } else {
+            float y = __builtin_fmaf(acc, k_acc, (kRel && UNI) ? uni + shift : shift);
+            if constexpr (kRel && !UNI) y += rel_entry(rp.dq);
+            return y;
+        }
+    }
+    // the relative-bias entry of q_idx - kv_idx = dq, times k_tab
+    __device__ __forceinline__ float rel_entry(int dq) const {
+        const int r = dq < 0 ? 0 : (dq > rel_max ? rel_max : dq);
+        if constexpr (LDSTAB) return *(const __attribute__((address_space(3))) float*)(uintptr_t)(tab_lds + 4u * (uint32_t)r);
+        else return tab[r] * k_tab;
+    }
+
     // A soft-capped score never exceeds the cap, so softmax can use the cap itself as its
     // (fixed) maximum when 2^(-2 cap log2 e) is still far from fp32 underflow: no running max,
     // no rescaling, and p = exp2(-2 capl2 r) directly.

@@ -190,6 +190,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
     // maximum is fixed at the cap from the start
     float m_run = BOUNDED ? smod.capl2 : -INFINITY, l_run = 0.0f;
     float m_use = 0.0f;     // the maximum the exponentials subtract: m_run, or 0 while the row has seen no key
+    float m_thr = -INFINITY; // what a block's largest shifted score must exceed for the maximum to move
 
     // score_mod, mask_mod (partial blocks only) and softmax of one 32-key block whose first key is
     // kvs: s -> P^T as two bf16 fragments.  The mask is a separate, rarely taken pass (kept a real
@@ -228,16 +229,20 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
                 for (int r = 0; r < 16; ++r) s[r] = keep(kvs + crow(r, half)) ? s[r] : 0.0f;
             }
         } else {
-            // A score_mod that only scales (the identity): the factor is positive, so the maximum can be
-            // taken over the raw dot products and the scaling folded into the exponent's multiply-add.
-            constexpr bool kScaleOnly = SCORE == FLEXATTN_SCORE_IDENTITY;
-            if constexpr (kScaleOnly) {
-            } else if (rel_is_uni) {
+            // Online softmax.  The running maximum only has to keep exp2(s - m) in range, so it follows
+            // the scores lazily: a row keeps its maximum until a block exceeds it by more than kLazyMax
+            // (P then reaches 2^kLazyMax at most, the row sum as much more; O / l and LSE = m + log2 l
+            // come out the same).  The score_mod therefore subtracts the CURRENT maximum on its way (folded
+            // into its multiply-adds), and only when some row of the wave moves its maximum -- rare after a
+            // row's first blocks -- are the scores shifted again and O^T and l rescaled.
+            constexpr float kLazyMax = 8.0f;
+            const float shift = -m_use;
+            if (rel_is_uni) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = smod.template apply<true>(s[r], rel(r), rel_uni);
+                for (int r = 0; r < 16; ++r) s[r] = smod.template apply_shifted<true>(s[r], rel(r), rel_uni, shift);
             } else {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = smod.template apply<false>(s[r], rel(r));
+                for (int r = 0; r < 16; ++r) s[r] = smod.template apply_shifted<false>(s[r], rel(r), 0.0f, shift);
             }
             if (partial) {
                 asm volatile("" ::: "memory");
@@ -248,18 +253,15 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
             mx = fmaxf(mx, swap_halves(mx));
-            if constexpr (kScaleOnly) mx *= smod.k_acc;
-            // The running maximum only has to keep exp2(s - m) in range, so it follows the scores lazily:
-            // a row keeps its old maximum until a block exceeds it by more than kLazyMax (P then reaches
-            // 2^kLazyMax at most, the row sum as much more; O / l and LSE = m + log2 l come out the same).
-            // On most blocks no row of the wave moves its maximum, and the rescaling of O^T is skipped.
-            constexpr float kLazyMax = 8.0f;
-            if (__any(mx > m_run + kLazyMax)) {      // some row of the wave moves its maximum
-                const float m_new = mx > m_run + kLazyMax ? mx : m_run;
-                const float m_new_use = (m_new == -INFINITY) ? 0.0f : m_new;
-                const float alpha = fast_exp2(m_run - m_new_use);   // 1 for the rows that stay, 0 for a row's first keys
-                m_run = m_new;
-                m_use = m_new_use;
+            if (__any(mx > m_thr)) {                 // some row of the wave moves its maximum (by mx)
+                const float up = mx > m_thr ? mx : 0.0f;
+                // (a row's first keys: nothing to rescale yet, and 2^-mx could overflow)
+                const float alpha = m_thr == -INFINITY ? 0.0f : fast_exp2(-up);
+                m_use += up;                         // (0 before the row's first key)
+                m_run = mx > m_thr ? m_use : m_run;
+                m_thr = mx > m_thr ? kLazyMax : m_thr;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] -= up;
                 l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db)
@@ -267,8 +269,7 @@ __global__ __launch_bounds__(NW * 64, (waves_per_simd<D, MASK, SCORE>())) void f
                     for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
             }
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                s[r] = fast_exp2(kScaleOnly ? __builtin_fmaf(s[r], smod.k_acc, -m_use) : s[r] - m_use);
+            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
         }
         // The row sum adds up the bf16-rounded probabilities, the values P V is computed from, two at
         // a time (dot product of a packed pair with (1, 1), fp32 accumulation).
