@@ -408,7 +408,8 @@ struct ScoreMod {
                                                  float (&g)[4], float (&p)[4], float uni = 0.0f) const {
         float x[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = pre<UNI>(acc[i], dq[i], uni);
+        for (int i = 0; i < 4; ++i)   // (without a soft-cap the row constant rides on the score_mod's multiply-adds)
+            x[i] = kCap ? pre<UNI>(acc[i], dq[i], uni) : apply_shifted<UNI>(acc[i], dq[i], uni, rc[i]);
         pin4(x);
         if constexpr (kCap) {
             float r[4];
@@ -428,11 +429,7 @@ struct ScoreMod {
             for (int i = 0; i < 4; ++i) g[i] = __builtin_fmaf(-r[i], r[i], r[i]);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                x[i] += rc[i];
-                g[i] = 1.0f;
-            }
-            pin4(x);
+            for (int i = 0; i < 4; ++i) g[i] = 1.0f;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) p[i] = fast_exp2(x[i]);
@@ -446,7 +443,7 @@ struct ScoreMod {
             return fast_exp2(__builtin_fmaf(-2.0f * capl2, r, rc));
         } else {
             g = 1.0f;
-            return fast_exp2(pre<UNI>(acc, dq, uni) + rc);
+            return fast_exp2(apply_shifted<UNI>(acc, dq, uni, rc));
         }
     }
 };
