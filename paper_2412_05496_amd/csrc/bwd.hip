@@ -38,8 +38,8 @@ bool stored_layout(const flexattn_dims* d, const flexattn_blockmask* bm, int64_t
     if (bm->Bq <= 0 || bm->Bk <= 0 || bm->Bm <= 0 || bm->Hm <= 0) return false;
     const int64_t NR = (d->q_len + bm->Bq - 1) / bm->Bq, NC = (d->kv_len + bm->Bk - 1) / bm->Bk;
     const int64_t planes = (int64_t)bm->Bm * bm->Hm, lines = planes * NC;
-    const int64_t cap = n_blocks > 0 ? n_blocks : 1;
-    if (lines >= (1ll << 30) || planes * NR * NC >= (1ll << 40) || cap * (bm->Bk / 64 + 1) >= (1ll << 31)) return false;
+    const int64_t cap = n_blocks > 0 ? n_blocks : 1;    // (times Bk / 64 tiles and Bq / 64 steps it must fit an int)
+    if (lines >= (1ll << 30) || planes * NR * NC >= (1ll << 40) || cap * 4 >= (1ll << 31)) return false;
     const int64_t reps = (int64_t)(bm->Bm > 1 ? 1 : d->B) * (bm->Hm > 1 ? 1 : d->Hq);
     out->cap = cap;
     out->lines = (int)lines;
