@@ -139,3 +139,27 @@ def test_decode_workspace_follows_the_split_length():
     assert ws(2, 4, 2, 64, 16, 4) == 2 * 4 * 1 * 66 * 4                    # shorter than one split
     assert ws(2, 4, 2, 64, 24, 4) == 0 and ws(2, 4, 2, 64, 2048, 4) == 0   # page sizes that are refused
     assert ws(2, 4, 2, 64, 8, 4) == 0
+
+
+def test_stored_backward_workspace_is_host_arithmetic():
+    """Row scalars (256-byte aligned), one int32 per column of blocks + 1, one per block position, then
+    2 * Bq * Bk bytes per block and per head that shares no BlockMask plane with an equal (b, hq)."""
+    lib = binding._lib()
+    al = lambda n: (n + 255) // 256 * 256
+    d = binding._Dims(4, 16, 16, 8192, 8192, 128)
+    bm = binding._BlockMask(1, 1, 8192, 8192, 128, 64)
+    NR, NC, n_blocks = 64, 128, 4160
+    want = al(2 * 4 * 16 * 8192 * 4) + al((NC + 1) * 4) + al(NR * NC * 4) + 4 * 16 * n_blocks * 128 * 64 * 2
+    assert lib.flexattn_backward_stored_workspace_bytes(C.byref(d), C.byref(bm), n_blocks) == want
+    # one plane per (b, hq): the planes' blocks are numbered through, nothing is stored twice
+    bm2 = binding._BlockMask(4, 16, 8192, 8192, 128, 64)
+    want2 = al(2 * 4 * 16 * 8192 * 4) + al((64 * NC + 1) * 4) + al(64 * NR * NC * 4) + 64 * n_blocks * 128 * 64 * 2
+    assert lib.flexattn_backward_stored_workspace_bytes(C.byref(d), C.byref(bm2), 64 * n_blocks) == want2
+    # no block at all still leaves room for one (slots are clamped into the capacity)
+    assert (lib.flexattn_backward_stored_workspace_bytes(C.byref(d), C.byref(bm), 0)
+            == lib.flexattn_backward_stored_workspace_bytes(C.byref(d), C.byref(bm), 1))
+    assert lib.flexattn_backward_stored_workspace_bytes(C.byref(d), C.byref(bm), -1) == 0
+    assert lib.flexattn_backward_stored_workspace_bytes(C.byref(d), C.byref(bm), 1 << 29) == 0
+    assert lib.flexattn_backward_stored_workspace_bytes(None, C.byref(bm), 1) == 0
+    assert lib.flexattn_backward_stored(C.byref(d), None, None, None, None, None, None, 0, 0, None, C.byref(bm), 1.0,
+                                        None, None, None, -1, None, 0, None, 7) == fa.ERR_INVALID_ARG
