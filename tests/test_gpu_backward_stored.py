@@ -157,3 +157,25 @@ def test_stored_capacity_and_workspace_errors():
     fa.flexattn_backward_stored(*args, small, ws)
     torch.cuda.synchronize()
     assert torch.isfinite(dQ.float()).all() and torch.isfinite(dK.float()).all() and torch.isfinite(dV.float()).all()
+
+
+def test_stored_strided_layout_and_stages_agree():
+    """[B, S, H, D] memory layout for every tensor, and the stages run one by one on one workspace, give bit
+    for bit what the dense single call gives."""
+    import paper_2412_05496_amd as fa
+    wl = SMALL["cfg2_small"].scaled(S=1000, Hq=4, Hkv=2)          # a cut last block and GQA as well
+    inp = wlm.make_train_inputs(wl, with_dO=True)
+    O, LSE, bm, ids = run_forward(wl, inp, DEV)
+    dQ, dK, dV = run_backward(wl, inp, DEV, O, LSE, bm, ids, stored=True)
+    mask_id, score_id, params, Q, K, V = ids
+    bshd = lambda t: t.transpose(1, 2).contiguous().transpose(1, 2)
+    Qs, Ks, Vs, Os, dOs = (bshd(t) for t in (Q, K, V, O, inp.dO.to(DEV)))
+    dQs, dKs, dVs = (bshd(torch.full_like(t, float("nan"))) for t in (Q, K, V))
+    n_blocks = nonempty_blocks(bm)
+    ws = torch.empty(fa.flexattn_backward_stored_workspace_bytes(Q, K, bm, n_blocks), dtype=torch.uint8, device=DEV)
+    for stage in (fa.BWD_DELTA, fa.BWD_DKDV, fa.BWD_DQ):
+        fa.flexattn_backward_stored(Qs, Ks, Vs, Os, dOs, LSE, score_id, mask_id, params, bm, inp.scale,
+                                    dQs if stage == fa.BWD_DQ else None, dKs if stage == fa.BWD_DKDV else None,
+                                    dVs if stage == fa.BWD_DKDV else None, n_blocks, ws, stage)
+    torch.cuda.synchronize()
+    assert torch.equal(dQs, dQ) and torch.equal(dKs, dK) and torch.equal(dVs, dV)

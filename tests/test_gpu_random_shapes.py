@@ -64,3 +64,10 @@ def test_random_shape(seed):
     hp.check_grad("dQ", dQ, dQ_ref)
     hp.check_grad("dK", dK, dK_ref)
     hp.check_grad("dV", dV, dV_ref)
+    # the same gradients with dS kept in memory: dK / dV from the same kernel, dQ from the stored blocks
+    dQ2, dK2, dV2 = torch.full_like(Qd, float("nan")), torch.full_like(Kd, float("nan")), torch.full_like(Vd, float("nan"))
+    fa.flexattn_backward_stored(Qd, Kd, Vd, O, dOd, LSE, score_id, mask_id, params, bm, inp.scale, dQ2, dK2, dV2,
+                                hp.nonempty_blocks(bm))
+    torch.cuda.synchronize()
+    assert torch.equal(dK2, dK) and torch.equal(dV2, dV)
+    hp.check_grad("dQ (dS kept in memory)", dQ2, dQ_ref)
