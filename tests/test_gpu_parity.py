@@ -265,3 +265,36 @@ def test_dkdv_walk_longer_than_one_segment(mask_name):
     g_ref = fo.flex_attention_backward(Q, K, V, dO, fo.Identity(), mask, scale)
     for n, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), g_ref):
         check_grad(n, g, r)
+
+
+@pytest.mark.parametrize("mask_name,D", [("causal", 128), ("none", 64)])
+def test_running_maximum_that_moves_late_and_far(mask_name, D):
+    """The forward moves a row's running maximum only when a block exceeds it by more than 2^8.  Keys whose
+    scores grow along the sequence (small steps that stay below the threshold, then jumps far above it) and a
+    first block of scores near -300 (whose 2^-max would overflow) must give the oracle's O and LSE."""
+    import paper_2412_05496_amd as fa
+    B, H, S = 1, 2, 1024
+    gen = torch.Generator().manual_seed(4242 + D)
+    Q = torch.randn(B, H, S, D, generator=gen)
+    K = torch.randn(B, H, S, D, generator=gen)
+    V = torch.randn(B, H, S, D, generator=gen)
+    ramp = torch.cat([torch.linspace(0.02, 0.6, 512), torch.linspace(0.6, 0.7, 256), torch.linspace(3.0, 6.0, 256)])
+    K = K * ramp.view(1, 1, S, 1)
+    # head 1: every query has a positive mean, the first 32 keys a large negative one: scores of about -300 there
+    Q[:, 1] = Q[:, 1] * 0.2 + 1.0
+    K[:, 1, :32] = -300.0 / D
+    Q, K, V = (t.to(torch.bfloat16).float() for t in (Q, K, V))
+    scale = 1.0 / D ** 0.5 * 4.0
+    mask = fo.causal_mask if mask_name == "causal" else fo.no_mask
+    O_ref, LSE_ref = fo.flex_attention(Q, K, V, fo.Identity(), mask, scale)
+    Qd, Kd, Vd = (t.to(torch.bfloat16).to(DEV) for t in (Q, K, V))
+    mask_id = fa.MASK_CAUSAL if mask_name == "causal" else fa.MASK_NONE
+    params = fa.ModParams()
+    bm = fa.alloc_blockmask(1, 1, S, S, 128, 64, device=DEV)
+    fa.flexattn_blockmask_build(mask_id, params, bm)
+    O = torch.full_like(Qd, float("nan"))
+    LSE = torch.full((B, H, S), float("nan"), dtype=torch.float32, device=DEV)
+    fa.flexattn_forward(Qd, Kd, Vd, fa.SCORE_IDENTITY, mask_id, params, bm, scale, O, LSE)
+    torch.cuda.synchronize()
+    print(f"[case] lazy maximum {mask_name} D={D}: LSE range {float(LSE_ref.min()):.1f} .. {float(LSE_ref.max()):.1f}", flush=True)
+    check_output(O, LSE, O_ref, LSE_ref)
