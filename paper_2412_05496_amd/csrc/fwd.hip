@@ -64,7 +64,7 @@ extern "C" const char* flexattn_strerror(int status) {
     }
 }
 extern "C" int flexattn_last_hip_error(void) { return g_last_hip_error; }
-extern "C" int flexattn_version(void) { return 110; }   // 110: work-order arrays in flexattn_blockmask, probes, static decode
+extern "C" int flexattn_version(void) { return 120; }   // 120: flexattn_backward_stored (110: work-order arrays, probes, static decode)
 extern "C" int flexattn_is_supported(uint32_t mask_id, uint32_t score_id, int32_t D) {
     return (D == 64 || D == 128) && find_variant(mask_id, score_id) >= 0;
 }
