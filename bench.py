@@ -14,6 +14,7 @@ The JSON line also carries
   roofline      the longest kernel of the step against the dense bf16 MFMA peak, timed with
                 events on the launch stream (`traffic` is the HBM byte count of that kernel from the
                 rocprofv3 --pmc runs recorded under profiles/, not a measurement of this run);
+  bwd_dq_roofline  the dQ kernel of the step's backward (a block-sparse GEMM over the stored dS) against the HBM peak;
   measured_peaks  what this chip sustains in this very run: an MFMA-only kernel and a plain
                 streaming read, so that every fraction can also be read against achievable rates;
   cfg3, cfg4    forward and backward of the document-mask + ALiBi and the sliding-window/prefix +
@@ -261,6 +262,15 @@ def main() -> int:
         "roofline": roofline,
     }
 
+    if stored:
+        # the dQ kernel of this path is a block-sparse GEMM bound by HBM: every dS block read once (2 bytes per
+        # score of a non-empty block), K once per head, dQ written once
+        dq_bytes = n_blocks * wl.Bq * wl.Bk * 2 * wl.B * wl.Hq + Kt.numel() * 2 + dQ.numel() * 2
+        dq_gbs = dq_bytes / (kt["bwd_dq"] * 1e-3) / 1e9
+        out["bwd_dq_roofline"] = {"kernel": "bwd_dq_stored", "bound": "hbm", "achieved": round(dq_gbs, 1),
+                                  "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(dq_gbs / PEAK_HBM_GBS, 4),
+                                  "traffic": measured_traffic("bwd_dq_stored"), "avg_ms": round(kt["bwd_dq"], 4),
+                                  "algorithmic_bytes": dq_bytes}
     if not args.one_bwd_path:
         # the library's other backward on the same inputs
         bwd_other()
@@ -320,6 +330,8 @@ def main() -> int:
         "bwd_frac_of_measured_mfma": round(out["bwd_tflops"] / mfma_tflops, 4),
         "roofline_frac_of_measured_mfma": round(achieved / mfma_tflops, 4),
     }
+    if "bwd_dq_roofline" in out:
+        out["bwd_dq_roofline"]["frac_of_measured_stream_read"] = round(out["bwd_dq_roofline"]["achieved"] / read_gbs, 4)
     out["roofline"]["traffic_source"] = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
                                          "this command, scaled by the copy calibration; not measured in this run")
 
