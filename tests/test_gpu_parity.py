@@ -145,6 +145,7 @@ def test_work_order_changes_no_result():
     assert not torch.equal(bm.kv_order, torch.arange(bm.kv_order.shape[-1] - 1, -1, -1, device=DEV,
                                                      dtype=torch.int32).expand_as(bm.kv_order))
     grads = run_backward(wl, inp, DEV, O, LSE, bm, ids)
+    grads_st = run_backward(wl, inp, DEV, O, LSE, bm, ids, stored=True)
     mask_id, score_id, params, Q, K, V = ids
     bm.kv_order, bm.q_order = None, None
     O2, LSE2 = torch.empty_like(O), torch.empty_like(LSE)
@@ -152,6 +153,8 @@ def test_work_order_changes_no_result():
     torch.cuda.synchronize()
     assert torch.equal(O, O2) and torch.equal(LSE, LSE2)
     for g1, g2 in zip(grads, run_backward(wl, inp, DEV, O2, LSE2, bm, ids)):
+        assert torch.equal(g1, g2)
+    for g1, g2 in zip(grads_st, run_backward(wl, inp, DEV, O2, LSE2, bm, ids, stored=True)):
         assert torch.equal(g1, g2)
 
 
