@@ -20,7 +20,10 @@
  *     device pointers as well.  Descriptor structs themselves are host memory, read during
  *     the call only.
  *   - Every launch is asynchronous on the caller's stream (`stream` is a hipStream_t passed
- *     as void*; NULL is the default stream).  No call synchronises.
+ *     as void*; NULL is the default stream).  No call synchronises, copies or clears memory
+ *     through the runtime: a call only launches kernels, so it may be made on a stream that
+ *     is being captured into a HIP graph (for flexattn_paged_decode_static after one call
+ *     outside a capture, which looks up the static array's address).
  *   - Float tensors are bf16 (Q, K, V, O, dO, dQ, dK, dV) unless stated; LSE is fp32.
  *     Head dimension D is 64 or 128 and has unit stride; other strides are in ELEMENTS.
  *   - Grouped-query attention: query head hq reads KV head hq / (Hq / Hkv); mods see hq.
