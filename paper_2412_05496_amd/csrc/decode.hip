@@ -5,7 +5,8 @@
 // KV split) and never synchronises with another: it walks its logical pages 32 keys at a time,
 // looks each key's page up in the page table and pulls the K and V rows straight from the pool into
 // its private, XOR-swizzled LDS tiles (global_load_lds_dwordx4: every wave instruction moves 1 KiB
-// of whole 256-byte rows, so the page gather is fully coalesced); the gather of the next tile is
+// of whole 256-byte rows, so the page gather is fully coalesced; non-temporal, since a decode step
+// reads every K / V row exactly once); the gather of the next tile is
 // started as soon as the current tile's operand fragments sit in registers.  S^T = K Q^T takes K rows from
 // LDS as the A operand with the G query heads of the group as (zero-padded) columns of the B
 // operand, so K and V are read once per KV head, never once per query head; V^T comes out of the
@@ -134,8 +135,8 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(const D
             const int tok = min(tok0 + row, ctx - 1);
             const int64_t off = ((int64_t)pg[i] * a.Hkv + hkv) * slab + (int64_t)(tok & page_mask) * D +
                                 (((lane % DC) ^ swz<D>(row)) * 8);
-            dma_global(lds_addr(k_tile + i * 512), a.K_pool + off);
-            dma_global(lds_addr(v_tile + i * 512), a.V_pool + off);
+            dma_global_nt(lds_addr(k_tile + i * 512), a.K_pool + off);
+            dma_global_nt(lds_addr(v_tile + i * 512), a.V_pool + off);
         }
     };
 

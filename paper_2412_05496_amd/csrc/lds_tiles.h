@@ -92,9 +92,11 @@ __device__ __forceinline__ void dma_x2(i32x4 rsrc, uint32_t lds, int v0, int v1,
                  :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(v0), "v"(v1), "s"(scalar_rsrc(rsrc)), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
-// 64 lanes x 16 bytes from per-lane global addresses to `lds` .. +1024.
-__device__ __forceinline__ void dma_global(uint32_t lds, const void* gptr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, off"
+// 64 lanes x 16 bytes from per-lane global addresses to `lds` .. +1024, with the non-temporal hint:
+// for data that is read exactly once (the K / V pages of a decode step), which then stream past the
+// caches instead of displacing each other there.
+__device__ __forceinline__ void dma_global_nt(uint32_t lds, const void* gptr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, off nt"
                  :: "s"(__builtin_amdgcn_readfirstlane(lds)), "v"(gptr) : "memory");
 }
 
